@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSR SpMM hot path on one MI355X.
+
+A "step" is one whole SpMM call (row-zeroing pass included where the point
+needs one) on a seeded synthetic workload that is resident in HBM.  All 28
+(group_size, strategy, schedule) points are swept briefly; the best one is
+then timed for exactly --steps steps and reported as ONE JSON line on stdout:
+effective GFLOP/s = 2*nnz*N/t, with the HBM roofline of the main kernel
+(minimal bytes nnz*8 + (M+1)*4 + K*N*4 + M*N*4 over its event-timed duration)
+and the CPU oracle timed on the host next to it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by the same counters on the library's plain copy kernel; keyed by
+# (workload, group, strategy, schedule).  See profiles/ for the runs.
+MEASURED_TRAFFIC_BYTES: dict = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_point(dp, torch, binding, C, point, iters):
+    g, st, sc = point
+    p = dp.p
+    args = (p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, g,
+            binding.STRATEGIES[st], binding.SCHEDULES[sc])
+    binding.sgap_spmm_csr_ex(*args)  # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        binding.sgap_spmm_csr_ex(*args)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / iters
+
+
+def cpu_baseline(p):
+    """The oracle as it stands, timed on this host: all cores on the whole
+    workload (static row split), and one core on the first quarter of the rows."""
+    import oracle
+
+    cores = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env))
+    t0 = time.perf_counter()
+    oracle.spmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, nthreads=cores)
+    t_all = time.perf_counter() - t0
+    rows = max(1, p.M // 4)
+    nnz_part = int(p.rowptr[rows])
+    t0 = time.perf_counter()
+    oracle.spmm_csr(rows, p.K, p.N, p.rowptr[:rows + 1], p.colidx[:nnz_part], p.vals[:nnz_part], p.B, nthreads=1)
+    t_one = time.perf_counter() - t0
+    return {
+        "value": 2.0 * p.nnz * p.N / t_all / 1e9,
+        "unit": "GFLOP/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"whole {p.name} workload, fp64 row-by-row oracle, static row split over {cores} threads",
+        "seconds": t_all,
+        "single_thread_gflops": 2.0 * nnz_part * p.N / t_one / 1e9,
+        "single_thread_sample": f"first {rows} rows",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="stencil27")
+    ap.add_argument("--sweep-iters", type=int, default=3)
+    ap.add_argument("--point", default=None, help="fix the point: e.g. 8,parallel,row_split (skips the sweep)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-out", default=None, help="write the per-point sweep table (JSON) to this file")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
+                 "(the path shards by row blocks without any exchange, see DESIGN.md)")
+
+    import torch
+
+    from paper_2209_02882_amd import binding
+    from paper_2209_02882_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.load()
+
+    t0 = time.perf_counter()
+    p = wl.make_problem(a.workload)
+    log(f"[bench] workload {a.workload}: {p.row_stats()} generated in {time.perf_counter() - t0:.1f}s")
+
+    from paper_2209_02882_amd.device import POINTS, DeviceProblem
+
+    dp = DeviceProblem(p)
+    C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
+    min_bytes = p.minimal_bytes()
+    flops = p.flops()
+
+    sweep = []
+    if a.point:
+        g, st, sc = a.point.split(",")
+        best = (int(g), st, sc)
+    else:
+        for pt in POINTS:
+            t = time_point(dp, torch, binding, C, pt, a.sweep_iters)
+            sweep.append({"group": pt[0], "strategy": pt[1], "schedule": pt[2], "ms": t * 1e3,
+                          "gflops": flops / t / 1e9, "gbs": min_bytes / t / 1e9,
+                          "hbm_frac": min_bytes / t / 1e9 / HBM_PEAK_GBS})
+            log(f"[sweep] g={pt[0]:2d} {pt[1]:8s} {pt[2]:12s} {t * 1e3:9.3f} ms "
+                f"{flops / t / 1e9:9.1f} GFLOP/s {min_bytes / t / 1e9:8.1f} GB/s")
+        b = min(sweep, key=lambda r: r["ms"])
+        best = (b["group"], b["strategy"], b["schedule"])
+    log(f"[bench] timing point {best}")
+
+    g, st, sc = best
+    args = (p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, g, binding.STRATEGIES[st], binding.SCHEDULES[sc])
+    for _ in range(a.warmup):
+        binding.sgap_spmm_csr_ex(*args)
+    binding.sgap_profile_enable(True)
+    binding.sgap_profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        binding.sgap_spmm_csr_ex(*args)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, n_ev = binding.sgap_profile_collect()
+    binding.sgap_profile_enable(False)
+    ms_per_step = elapsed / a.steps * 1e3
+    kernel_avg_ms = kernel_ms / max(1, n_ev)
+
+    # streaming reference: the library's plain copy kernel over 1 GiB
+    n_copy = 256 * 1024 * 1024
+    src = torch.empty(n_copy, dtype=torch.float32, device="cuda:0").fill_(1.0)
+    dst = torch.empty_like(src)
+    binding.sgap_copy_f32(src, dst)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        binding.sgap_copy_f32(src, dst)
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * n_copy * 4 * 10 / (time.perf_counter() - t0) / 1e9
+    del src, dst
+
+    achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "SpMM effective GFLOP/s (2*nnz*N/t), fp32, best (group_size, strategy, schedule) point",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": a.workload, "M": p.M, "K": p.K, "N": p.N, "nnz": p.nnz,
+                   "group_size": g, "strategy": st, "schedule": sc},
+        "hbm_gbs_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
+        "hbm_frac_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "copy_kernel_gbs": copy_gbs,
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc)),
+            "kernel_avg_ms": kernel_avg_ms,
+            "algorithmic_bytes": min_bytes,
+        },
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p)
+    if a.sweep_out and sweep:
+        with open(a.sweep_out, "w") as f:
+            json.dump({"workload": a.workload, "stats": p.row_stats(), "points": sweep}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

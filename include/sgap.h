@@ -1,0 +1,172 @@
+/*
+ * sgap.h - C ABI of the MI355X (gfx950) CSR SpMM library.
+ *
+ *   C[M,N] = A_csr[M,K] * B[K,N]      fp32, A in CSR, B and C dense row-major
+ *
+ * The operation is the SpMM form of the paper's sparse-dense hybrid algebra
+ * (Section 2.1, last of the forms listed under Eq. 1).  How the sum over a
+ * row's stored entries is organised follows the paper's "atomic parallelism"
+ * design space (Section 3) through the "segment group" abstraction
+ * (Section 4): a group of `group_size` lanes is the unit of synchronisation,
+ * and `strategy` says how a group turns per-lane products into row sums.
+ * Every (group_size, strategy, schedule) point computes the same C; only the
+ * order of fp32 additions differs.
+ *
+ * Conventions for every entry point
+ *   - All array arguments are DEVICE pointers owned by the caller.  The
+ *     library reads rowptr/colidx/vals/B, overwrites C, keeps no pointer
+ *     after the call returns and allocates no device memory.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without waiting.
+ *   - Return value: an sgap_status.  On anything but SGAP_OK nothing was
+ *     launched and C is untouched; sgap_last_error() gives detail.
+ *   - Preconditions that are NOT checked on the device: rowptr[0] == 0,
+ *     rowptr non-decreasing, rowptr[M] == number of stored entries,
+ *     0 <= colidx[p] < K.  Column indices inside a row need not be sorted
+ *     or distinct (duplicates add).  Explicit zeros are ordinary entries.
+ *   - Indices are 0-based int32; element offsets are formed in 64 bits.
+ *   - Semantics are OVERWRITE (C = A*B): rows without stored entries become
+ *     +0, whatever C held before.  A row's result may be -0 or +0 where the
+ *     exact sum is zero.
+ */
+#ifndef SGAP_H
+#define SGAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SGAP_OK = 0,
+    SGAP_ERR_INVALID_ARG = 1, /* bad size, enum, group size or null pointer   */
+    SGAP_ERR_UNSUPPORTED = 2, /* valid request this build cannot serve        */
+    SGAP_ERR_HIP = 3          /* the HIP runtime reported an error on launch  */
+} sgap_status;
+
+/*
+ * Reduction strategy of a segment group (Section 4.2 "ReductionStrategy";
+ * the parallel / serial axis of Section 3.3's mapping to earlier SpMM
+ * algorithm spaces).
+ *
+ * SGAP_REDUCE_PARALLEL: group_size lanes of one wavefront each take a share
+ *   of the stored entries and combine their partial sums with cross-lane
+ *   operations.
+ *     row-split schedule   : the group_size lanes share one row
+ *       ({<1/g row, c col>, r} with g = r = group_size, Section 6.2); a plain
+ *       tree sum, one writeback lane, plain store.
+ *     nnz-balanced schedule: lane = one stored entry ({<1 nnz, c col>, r},
+ *       Section 6.2); the group performs a SEGMENTED reduction keyed by row
+ *       (Fig. 1c), one writeback lane per run of equal rows.
+ * SGAP_REDUCE_SERIAL: reduction parallelism 1.  Each lane walks group_size
+ *   consecutive units by itself and flushes its register when the row changes
+ *   ("conditional" reduction).
+ *     row-split schedule   : lane = group_size consecutive rows
+ *       ({<g row, c col>, 1}, Section 6.1), plain stores.
+ *     nnz-balanced schedule: lane = group_size consecutive stored entries
+ *       ({<g nnz, c col>, 1}, Section 6.1).
+ *
+ * In the nnz-balanced schedule a row whose entries all lie inside one aligned
+ * block of group_size positions is written with a plain store; any other
+ * non-empty row is zeroed first and receives its partial sums by atomic adds.
+ */
+typedef enum { SGAP_REDUCE_PARALLEL = 0, SGAP_REDUCE_SERIAL = 1 } sgap_strategy;
+
+/*
+ * Work partition (Section 3.2: minimal data counted in rows or in non-zeros).
+ * SGAP_SCHED_ROW_SPLIT   : units of work are rows of A.
+ * SGAP_SCHED_NNZ_BALANCED: units of work are equal runs of stored entries;
+ *   the row of an entry is found by searching rowptr (Listings 1 and 2).
+ */
+typedef enum { SGAP_SCHED_ROW_SPLIT = 0, SGAP_SCHED_NNZ_BALANCED = 1 } sgap_schedule;
+
+/* Process-wide schedule used by sgap_spmm_csr(); default SGAP_SCHED_ROW_SPLIT.
+ * sgap_set_schedule returns SGAP_ERR_INVALID_ARG for an unknown value. */
+int sgap_set_schedule(int schedule);
+int sgap_get_schedule(void);
+
+/*
+ * C = A*B with the process-wide schedule.
+ *   M, K, N     rows of A and C; columns of A = rows of B; columns of B and C.
+ *               All >= 0, M <= 2^31-2, N < 2^31.  M == 0 or N == 0: SGAP_OK,
+ *               nothing to do.
+ *   rowptr      device, int32[M+1]
+ *   colidx      device, int32[rowptr[M]]   (may be NULL only if A is known
+ *               empty, i.e. never dereferenced when rowptr[M] == 0)
+ *   vals        device, fp32[rowptr[M]]
+ *   B           device, fp32[K*N], row-major, leading dimension N
+ *   C           device, fp32[M*N], row-major, leading dimension N; overwritten
+ *   group_size  1, 2, 4, 8, 16, 32 or 64 (lanes of a wave64 segment group for
+ *               SGAP_REDUCE_PARALLEL; units per lane for SGAP_REDUCE_SERIAL)
+ *   strategy    an sgap_strategy
+ *   stream      hipStream_t or NULL
+ * The number of dense columns per lane (the paper's c) is chosen from N and
+ * the pointer alignment: 4 (one 16-byte load) if N % 4 == 0 and B, C are
+ * 16-byte aligned, else 2, else 1 (Section 7.2, coarsening rule).
+ * The nnz-balanced schedule reads rowptr[M] on the device and runs a
+ * fixed-size grid, so this call never synchronises with the host.
+ */
+int sgap_spmm_csr(int64_t M, int64_t K, int64_t N,
+                  const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                  const float* B, float* C,
+                  int group_size, int strategy, void* stream);
+
+/*
+ * Same, with the schedule passed explicitly (no process-wide state) and an
+ * optional host-side count of stored entries.
+ *   schedule    an sgap_schedule
+ *   nnz_hint    rowptr[M] if the caller knows it, else -1.  Only used to size
+ *               the nnz-balanced grid (a hint larger than the truth is safe;
+ *               a smaller one is also safe, only slower).
+ */
+int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N,
+                     const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                     const float* B, float* C,
+                     int group_size, int strategy, int schedule,
+                     int64_t nnz_hint, void* stream);
+
+/* Text for a status code / detail of this thread's last failure (static or
+ * thread-local storage; never free). */
+const char* sgap_status_string(int status);
+const char* sgap_last_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sgap_version(void);
+
+/*
+ * Timing hooks for benchmarks.  While enabled, every sgap_spmm_csr* call
+ * brackets its main SpMM kernel (not the row-zeroing pass) with a pair of HIP
+ * events on the call's stream.  sgap_profile_collect waits for those events,
+ * adds their elapsed times in milliseconds into *total_ms, their number into
+ * *count, and forgets them.  Not thread-safe; host pointers.
+ */
+int sgap_profile_enable(int on);
+int sgap_profile_collect(double* total_ms, int* count);
+
+/*
+ * Device self-checks of the two cross-lane primitives behind the strategies
+ * (the paper's macro instructions atomicAddGroup<T,G> and
+ * segReduceGroup<T,G>, Section 5.3), one wavefront each.  `lanes_per_row`
+ * (1..64/group_size, power of two) is the lane stride between neighbouring
+ * members of a group.
+ *   sgap_debug_group_reduce: in fp32[64] device -> out fp32[64] device; the
+ *     first lane of every group receives the sum of its group's inputs, other
+ *     lanes receive 0.
+ *   sgap_debug_group_seg_reduce: in fp32[64], span int32[64] device (span[l] =
+ *     how many following members of lane l's group continue lane l's run,
+ *     0..group_size-1) -> out[l] = in[l] + the next span[l] members' inputs.
+ */
+int sgap_debug_group_reduce(const float* in, float* out, int group_size,
+                            int lanes_per_row, void* stream);
+int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out,
+                                int group_size, int lanes_per_row, void* stream);
+
+/* Plain device-to-device fp32 copy kernel (n elements).  Used to calibrate
+ * hardware traffic counters and to report a streaming-bandwidth reference. */
+int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGAP_H */

@@ -1,0 +1,181 @@
+"""ctypes binding of libsgap.so: argument marshalling only.
+
+Function names mirror the C ABI in include/sgap.h.  Tensors are torch CUDA
+tensors (used purely as device memory); every computation happens in the HIP
+kernels of the library.  There is no fallback: if the shared library is not
+built, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsgap.so")
+
+SGAP_OK = 0
+SGAP_ERR_INVALID_ARG = 1
+SGAP_ERR_UNSUPPORTED = 2
+SGAP_ERR_HIP = 3
+
+SGAP_REDUCE_PARALLEL = 0
+SGAP_REDUCE_SERIAL = 1
+SGAP_SCHED_ROW_SPLIT = 0
+SGAP_SCHED_NNZ_BALANCED = 1
+
+STRATEGIES = {"parallel": SGAP_REDUCE_PARALLEL, "serial": SGAP_REDUCE_SERIAL}
+SCHEDULES = {"row_split": SGAP_SCHED_ROW_SPLIT, "nnz_balanced": SGAP_SCHED_NNZ_BALANCED}
+GROUP_SIZES = (1, 2, 4, 8, 16, 32, 64)
+
+# every symbol include/sgap.h declares: name -> (restype, argtypes)
+_i64, _int, _p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+EXPORTS = {
+    "sgap_set_schedule": (_int, [_int]),
+    "sgap_get_schedule": (_int, []),
+    "sgap_spmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _p]),
+    "sgap_spmm_csr_ex": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
+    "sgap_status_string": (ctypes.c_char_p, [_int]),
+    "sgap_last_error": (ctypes.c_char_p, []),
+    "sgap_version": (_int, []),
+    "sgap_profile_enable": (_int, [_int]),
+    "sgap_profile_collect": (_int, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_int)]),
+    "sgap_debug_group_reduce": (_int, [_p, _p, _int, _int, _p]),
+    "sgap_debug_group_seg_reduce": (_int, [_p, _p, _p, _int, _int, _p]),
+    "sgap_copy_f32": (_int, [_p, _p, _i64, _p]),
+}
+
+_lib = None
+
+
+class SgapError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"sgap status {status} ({what})")
+        self.status = status
+
+
+def load():
+    """Load libsgap.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2209_02882_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != SGAP_OK:
+        lib = load()
+        what = lib.sgap_status_string(status).decode()
+        detail = lib.sgap_last_error().decode()
+        raise SgapError(status, f"{what}: {detail}" if detail else what)
+
+
+def _dev_ptr(t, dtype, name):
+    import torch
+
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor (device memory)")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr() if t.numel() else None
+
+
+def _stream_ptr(stream):
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def sgap_version() -> int:
+    return load().sgap_version()
+
+
+def sgap_set_schedule(schedule: int) -> None:
+    _check(load().sgap_set_schedule(int(schedule)))
+
+
+def sgap_get_schedule() -> int:
+    return load().sgap_get_schedule()
+
+
+def _spmm_args(M, K, N, rowptr, colidx, vals, B, C):
+    import torch
+
+    if rowptr.numel() != M + 1:
+        raise ValueError("rowptr must have M+1 entries")
+    if colidx.numel() != vals.numel():
+        raise ValueError("colidx and vals must have the same length")
+    if B.numel() != K * N or C.numel() != M * N:
+        raise ValueError("B must hold K*N and C must hold M*N elements")
+    return (
+        _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+        _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"),
+        _dev_ptr(C, torch.float32, "C"))
+
+
+def sgap_spmm_csr(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, stream=None) -> None:
+    """C = A_csr * B with the process-wide schedule (see include/sgap.h)."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    _check(load().sgap_spmm_csr(M, K, N, *ptrs, int(group_size), int(strategy), _stream_ptr(stream)))
+
+
+def sgap_spmm_csr_ex(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, schedule,
+                     nnz_hint=None, stream=None) -> None:
+    """C = A_csr * B with an explicit schedule.  nnz_hint defaults to the
+    length of colidx, which the host knows without touching the device."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    _check(load().sgap_spmm_csr_ex(M, K, N, *ptrs, int(group_size), int(strategy), int(schedule),
+                                   int(nnz_hint), _stream_ptr(stream)))
+
+
+def sgap_profile_enable(on: bool) -> None:
+    _check(load().sgap_profile_enable(1 if on else 0))
+
+
+def sgap_profile_collect():
+    """(total milliseconds, number of timed main-kernel launches) since the last collect."""
+    total = ctypes.c_double(0.0)
+    count = ctypes.c_int(0)
+    _check(load().sgap_profile_collect(ctypes.byref(total), ctypes.byref(count)))
+    return total.value, count.value
+
+
+def sgap_debug_group_reduce(inp, out, group_size, lanes_per_row, stream=None) -> None:
+    import torch
+
+    _check(load().sgap_debug_group_reduce(
+        _dev_ptr(inp, torch.float32, "in"), _dev_ptr(out, torch.float32, "out"),
+        int(group_size), int(lanes_per_row), _stream_ptr(stream)))
+
+
+def sgap_debug_group_seg_reduce(inp, span, out, group_size, lanes_per_row, stream=None) -> None:
+    import torch
+
+    _check(load().sgap_debug_group_seg_reduce(
+        _dev_ptr(inp, torch.float32, "in"), _dev_ptr(span, torch.int32, "span"),
+        _dev_ptr(out, torch.float32, "out"), int(group_size), int(lanes_per_row), _stream_ptr(stream)))
+
+
+def sgap_copy_f32(src, dst, n=None, stream=None) -> None:
+    import torch
+
+    if n is None:
+        n = src.numel()
+    if n > src.numel() or n > dst.numel():
+        raise ValueError("copy length exceeds a buffer")
+    _check(load().sgap_copy_f32(_dev_ptr(src, torch.float32, "src"), _dev_ptr(dst, torch.float32, "dst"),
+                                int(n), _stream_ptr(stream)))

@@ -1,0 +1,314 @@
+// C ABI of the library: argument validation, choice of kernel instance,
+// launches on the caller's stream.  See include/sgap.h for the contract.
+#include "../../include/sgap.h"
+
+#include <cstdio>
+#include <cstring>
+#include <utility>
+#include <vector>
+
+#include "sgap_common.hpp"
+#include "sgap_lane_ops.hpp"
+
+namespace sgap {
+
+// ---- small kernels that belong to the boundary, not to a schedule ---------
+
+template <int G, int LC>
+__global__ void debug_group_reduce_kernel(const float* __restrict__ in, float* __restrict__ out)
+{
+    const int lane = threadIdx.x;
+    const float s = group_tree_sum<G, LC>(in[lane]);
+    const int member = (lane / LC) % G;
+    out[lane] = member == 0 ? s : 0.0f;
+}
+
+template <int G, int LC>
+__global__ void debug_group_seg_reduce_kernel(const float* __restrict__ in, const int32_t* __restrict__ span,
+                                              float* __restrict__ out)
+{
+    const int lane = threadIdx.x;
+    out[lane] = group_seg_sum<G, LC>(in[lane], span[lane]);
+}
+
+__global__ __launch_bounds__(kBlock) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                          int64_t n)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+    for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+namespace {
+struct LaunchDebugReduce {
+    const float* in;
+    float* out;
+    hipStream_t s;
+    template <int G, int LC, int VEC>
+    void operator()() const
+    {
+        hipLaunchKernelGGL((debug_group_reduce_kernel<G, LC>), dim3(1), dim3(kWave), 0, s, in, out);
+    }
+};
+struct LaunchDebugSegReduce {
+    const float* in;
+    const int32_t* span;
+    float* out;
+    hipStream_t s;
+    template <int G, int LC, int VEC>
+    void operator()() const
+    {
+        hipLaunchKernelGGL((debug_group_seg_reduce_kernel<G, LC>), dim3(1), dim3(kWave), 0, s, in, span, out);
+    }
+};
+}  // namespace
+
+hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s)
+{
+    if (!dispatch_group(g, lc, 1, LaunchDebugReduce{in, out, s})) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
+                                         hipStream_t s)
+{
+    if (!dispatch_group(g, lc, 1, LaunchDebugSegReduce{in, span, out, s})) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s)
+{
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(256 * 16), dim3(kBlock), 0, s, src, dst, n);
+    return hipGetLastError();
+}
+
+}  // namespace sgap
+
+// ---------------------------------------------------------------------------
+
+namespace {
+
+int g_schedule = SGAP_SCHED_ROW_SPLIT;
+thread_local char t_last_error[256] = "";
+
+bool g_profile = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
+
+int fail(int status, const char* fmt, const char* detail = "")
+{
+    std::snprintf(t_last_error, sizeof(t_last_error), fmt, detail);
+    return status;
+}
+
+bool is_pow2_group(int g) { return g >= 1 && g <= 64 && (g & (g - 1)) == 0; }
+
+int ilog2(int v)
+{
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+int pow2_ceil_capped(int64_t v, int cap)
+{
+    int r = 1;
+    while (r < cap && r < v) r *= 2;
+    return r;
+}
+
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+              const float* B, float* C, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream)
+{
+    using namespace sgap;
+    if (M < 0 || K < 0 || N < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
+    if (M > 2147483646LL || N > 2147483647LL || K > 2147483647LL)
+        return fail(SGAP_ERR_INVALID_ARG, "dimension exceeds int32 index range");
+    if (!is_pow2_group(group_size)) return fail(SGAP_ERR_INVALID_ARG, "group_size must be 1,2,4,8,16,32 or 64");
+    if (strategy != SGAP_REDUCE_PARALLEL && strategy != SGAP_REDUCE_SERIAL)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
+    if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
+    if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
+    if (M == 0 || N == 0) return SGAP_OK;
+    if (!rowptr || !C) return fail(SGAP_ERR_INVALID_ARG, "rowptr and C must not be null");
+    if (K > 0 && !B) return fail(SGAP_ERR_INVALID_ARG, "B must not be null when K > 0");
+    if (nnz_hint != 0 && K > 0 && (!colidx || !vals) && nnz_hint > 0)
+        return fail(SGAP_ERR_INVALID_ARG, "colidx and vals must not be null when A has entries");
+
+    // columns per lane (coarsening c): widest vector the shape and alignment allow
+    const uintptr_t align_bits = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
+    int vec = 1;
+    if (N % 4 == 0 && (align_bits & 15) == 0) vec = 4;
+    else if (N % 2 == 0 && (align_bits & 7) == 0) vec = 2;
+    const int64_t chunks = (N + vec - 1) / vec;
+
+    SpmmArgs a;
+    a.M = M; a.K = K; a.N = N;
+    a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.B = B; a.C = C;
+    a.group = group_size;
+    a.log2_group = ilog2(group_size);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipError_t err = hipSuccess;
+    auto mark = [&](hipEvent_t& ev) {
+        if (g_profile && hipEventCreate(&ev) == hipSuccess) hipEventRecord(ev, s);
+    };
+
+    if (schedule == SGAP_SCHED_ROW_SPLIT) {
+        if (strategy == SGAP_REDUCE_PARALLEL) {
+            const int lc = pow2_ceil_capped(chunks, 64 / group_size);
+            mark(ev0);
+            err = launch_row_split_parallel(a, lc, vec, s);
+        } else {
+            const int lc = pow2_ceil_capped(chunks, 64);
+            mark(ev0);
+            err = launch_row_split_serial(a, lc, vec, s);
+        }
+    } else {
+        // persistent grid: a few workgroups per compute unit, fewer if the
+        // caller told us A is small
+        int grid = compute_units() * 8;
+        if (nnz_hint >= 0) {
+            const int64_t tiles = (nnz_hint + 1023) / 1024;
+            if (tiles < grid) grid = tiles > 0 ? (int)tiles : 1;
+        }
+        err = launch_nnz_zero_rows(a, vec, s);
+        if (err == hipSuccess) {
+            if (strategy == SGAP_REDUCE_PARALLEL) {
+                const int lc = pow2_ceil_capped(chunks, 64 / group_size);
+                mark(ev0);
+                err = launch_nnz_parallel(a, lc, vec, grid, s);
+            } else {
+                const int lc = pow2_ceil_capped(chunks, 64);
+                mark(ev0);
+                err = launch_nnz_serial(a, lc, vec, grid, s);
+            }
+        }
+    }
+    if (ev0) {
+        mark(ev1);
+        if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);
+    }
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sgap_set_schedule(int schedule)
+{
+    if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
+    g_schedule = schedule;
+    return SGAP_OK;
+}
+
+int sgap_get_schedule(void) { return g_schedule; }
+
+int sgap_spmm_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                  const float* B, float* C, int group_size, int strategy, void* stream)
+{
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, g_schedule, -1, stream);
+}
+
+int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                     const float* vals, const float* B, float* C, int group_size, int strategy, int schedule,
+                     int64_t nnz_hint, void* stream)
+{
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, schedule, nnz_hint, stream);
+}
+
+const char* sgap_status_string(int status)
+{
+    switch (status) {
+        case SGAP_OK: return "ok";
+        case SGAP_ERR_INVALID_ARG: return "invalid argument";
+        case SGAP_ERR_UNSUPPORTED: return "unsupported";
+        case SGAP_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* sgap_last_error(void) { return t_last_error; }
+
+int sgap_version(void) { return 100; }
+
+int sgap_profile_enable(int on)
+{
+    g_profile = on != 0;
+    return SGAP_OK;
+}
+
+int sgap_profile_collect(double* total_ms, int* count)
+{
+    double total = 0.0;
+    int n = 0;
+    int status = SGAP_OK;
+    for (auto& ev : g_events) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(ev.second) == hipSuccess && hipEventElapsedTime(&ms, ev.first, ev.second) == hipSuccess) {
+            total += ms;
+            ++n;
+        } else {
+            status = fail(SGAP_ERR_HIP, "could not read profiling events");
+        }
+        hipEventDestroy(ev.first);
+        hipEventDestroy(ev.second);
+    }
+    g_events.clear();
+    if (total_ms) *total_ms = total;
+    if (count) *count = n;
+    return status;
+}
+
+int sgap_debug_group_reduce(const float* in, float* out, int group_size, int lanes_per_row, void* stream)
+{
+    if (!in || !out || !is_pow2_group(group_size) || !is_pow2_group(lanes_per_row) ||
+        group_size * lanes_per_row > 64)
+        return fail(SGAP_ERR_INVALID_ARG, "bad group layout");
+    hipError_t err = sgap::launch_debug_group_reduce(in, out, group_size, lanes_per_row,
+                                                     reinterpret_cast<hipStream_t>(stream));
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int group_size, int lanes_per_row,
+                                void* stream)
+{
+    if (!in || !span || !out || !is_pow2_group(group_size) || !is_pow2_group(lanes_per_row) ||
+        group_size * lanes_per_row > 64)
+        return fail(SGAP_ERR_INVALID_ARG, "bad group layout");
+    hipError_t err = sgap::launch_debug_group_seg_reduce(in, span, out, group_size, lanes_per_row,
+                                                         reinterpret_cast<hipStream_t>(stream));
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream)
+{
+    if (n < 0 || (n > 0 && (!src || !dst))) return fail(SGAP_ERR_INVALID_ARG, "bad copy arguments");
+    if (n == 0) return SGAP_OK;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)
+        return fail(SGAP_ERR_INVALID_ARG, "copy buffers must be 16-byte aligned");
+    hipError_t err = sgap::launch_copy_f32(src, dst, n, reinterpret_cast<hipStream_t>(stream));
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Shared declarations of the SpMM kernels: argument block, per-lane column
+// vectors (the paper's coarsening factor c = VEC dense columns per lane) and
+// the host-side launch entry points of each kernel family.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sgap {
+
+constexpr int kWave = 64;          // wavefront size on gfx950
+constexpr int kBlock = 256;        // threads per workgroup (4 waves)
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+struct SpmmArgs {
+    int64_t M, K, N;
+    const int32_t* __restrict__ rowptr;
+    const int32_t* __restrict__ colidx;
+    const float* __restrict__ vals;
+    const float* __restrict__ B;
+    float* __restrict__ C;
+    int log2_group;   // log2(group_size)
+    int group;        // group_size
+};
+
+template <int VEC>
+struct Vec {
+    float v[VEC];
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = 0.0f;
+    }
+    __device__ __forceinline__ void fma(float a, const Vec& b)
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = __builtin_fmaf(a, b.v[i], v[i]);
+    }
+};
+
+// VEC consecutive floats starting at an address aligned to VEC*4 bytes.
+template <int VEC>
+__device__ __forceinline__ Vec<VEC> load_vec(const float* __restrict__ p)
+{
+    Vec<VEC> r;
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else if constexpr (VEC == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(p);
+        r.v[0] = t.x; r.v[1] = t.y;
+    } else {
+        r.v[0] = *p;
+    }
+    return r;
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float* __restrict__ p, const Vec<VEC>& r)
+{
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4*>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2*>(p) = make_float2(r.v[0], r.v[1]);
+    } else {
+        *p = r.v[0];
+    }
+}
+
+// Cross-group merge: hardware fp32 atomic add (no return value needed).
+template <int VEC>
+__device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<VEC>& r)
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(p + i, r.v[i]);
+}
+
+// ---- host-side launchers, one per kernel family (defined in the .hip files)
+// lc = chunk lanes per row (power of two), vec = columns per lane (1, 2, 4).
+hipError_t launch_row_split_parallel(const SpmmArgs& a, int lc, int vec, hipStream_t s);
+hipError_t launch_row_split_serial(const SpmmArgs& a, int lc, int vec, hipStream_t s);
+hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, hipStream_t s);
+hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int grid, hipStream_t s);
+hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int grid, hipStream_t s);
+hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s);
+hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
+                                         hipStream_t s);
+hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s);
+
+// Generic (g, lc, vec) -> template instance dispatch.  F is a functor with
+//   template <int G, int LC, int VEC> void operator()() const
+template <int G, int LC, typename F>
+inline bool dispatch_vec(int vec, F&& f)
+{
+    switch (vec) {
+        case 4: f.template operator()<G, LC, 4>(); return true;
+        case 2: f.template operator()<G, LC, 2>(); return true;
+        case 1: f.template operator()<G, LC, 1>(); return true;
+        default: return false;
+    }
+}
+
+template <int G, typename F>
+inline bool dispatch_lc(int lc, int vec, F&& f)
+{
+    switch (lc) {
+        case 1: if constexpr (G * 1 <= 64) return dispatch_vec<G, 1>(vec, f); break;
+        case 2: if constexpr (G * 2 <= 64) return dispatch_vec<G, 2>(vec, f); break;
+        case 4: if constexpr (G * 4 <= 64) return dispatch_vec<G, 4>(vec, f); break;
+        case 8: if constexpr (G * 8 <= 64) return dispatch_vec<G, 8>(vec, f); break;
+        case 16: if constexpr (G * 16 <= 64) return dispatch_vec<G, 16>(vec, f); break;
+        case 32: if constexpr (G * 32 <= 64) return dispatch_vec<G, 32>(vec, f); break;
+        case 64: if constexpr (G * 64 <= 64) return dispatch_vec<G, 64>(vec, f); break;
+        default: break;
+    }
+    return false;
+}
+
+template <typename F>
+inline bool dispatch_group(int g, int lc, int vec, F&& f)
+{
+    switch (g) {
+        case 1: return dispatch_lc<1>(lc, vec, f);
+        case 2: return dispatch_lc<2>(lc, vec, f);
+        case 4: return dispatch_lc<4>(lc, vec, f);
+        case 8: return dispatch_lc<8>(lc, vec, f);
+        case 16: return dispatch_lc<16>(lc, vec, f);
+        case 32: return dispatch_lc<32>(lc, vec, f);
+        case 64: return dispatch_lc<64>(lc, vec, f);
+        default: return false;
+    }
+}
+
+}  // namespace sgap

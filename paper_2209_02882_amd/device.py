@@ -1,0 +1,46 @@
+"""Device-side plumbing for tests and the benchmark: upload a problem into
+HBM (torch tensors as device memory) and run one design-space point through
+the C ABI.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import torch
+
+from . import binding
+
+# every (group_size, strategy, schedule) point of the design space
+POINTS = [(g, st, sc) for sc in ("row_split", "nnz_balanced") for st in ("parallel", "serial")
+          for g in binding.GROUP_SIZES]
+
+
+class DeviceProblem:
+    def __init__(self, p, device="cuda:0"):
+        self.p = p
+        dev = torch.device(device)
+        self.rowptr = torch.from_numpy(p.rowptr).to(dev)
+        self.colidx = torch.from_numpy(p.colidx).to(dev)
+        self.vals = torch.from_numpy(p.vals).to(dev)
+        self.B = torch.from_numpy(p.B).to(dev)
+
+    def new_output(self, poison=False):
+        C = torch.empty((self.p.M, self.p.N), dtype=torch.float32, device=self.rowptr.device)
+        if poison:
+            C.fill_(float("nan"))
+        return C
+
+    def launch(self, C, group, strategy, schedule, nnz_hint=None, stream=None):
+        """Enqueue C = A*B for one point (asynchronous)."""
+        p = self.p
+        binding.sgap_spmm_csr_ex(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, self.B, C,
+                                 group, binding.STRATEGIES[strategy], binding.SCHEDULES[schedule],
+                                 nnz_hint=nnz_hint, stream=stream)
+
+    def run(self, group, strategy, schedule, poison=True, C=None, nnz_hint=None):
+        """Run one point to completion; by default C starts filled with NaN so
+        that any element the kernels fail to write is visible."""
+        if C is None:
+            C = self.new_output()
+        if poison:
+            C.fill_(float("nan"))
+        self.launch(C, group, strategy, schedule, nnz_hint=nnz_hint)
+        torch.cuda.synchronize()
+        return C

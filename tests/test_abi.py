@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2209_02882_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sgap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sgap_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    lib = binding.load()
+    names = declared_symbols()
+    assert "sgap_spmm_csr" in names and "sgap_spmm_csr_ex" in names
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in sgap.h but not exported"
+        assert name in binding.EXPORTS, f"{name} has no Python binding signature"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_status_strings():
+    lib = binding.load()
+    assert lib.sgap_version() >= 100
+    assert lib.sgap_status_string(0) == b"ok"
+    assert lib.sgap_status_string(1) == b"invalid argument"
+    assert lib.sgap_status_string(77) == b"unknown status"
+
+
+def test_schedule_selector():
+    lib = binding.load()
+    assert lib.sgap_get_schedule() == binding.SGAP_SCHED_ROW_SPLIT
+    assert lib.sgap_set_schedule(binding.SGAP_SCHED_NNZ_BALANCED) == 0
+    assert lib.sgap_get_schedule() == binding.SGAP_SCHED_NNZ_BALANCED
+    assert lib.sgap_set_schedule(5) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_get_schedule() == binding.SGAP_SCHED_NNZ_BALANCED
+    assert lib.sgap_set_schedule(binding.SGAP_SCHED_ROW_SPLIT) == 0
+
+
+@pytest.mark.parametrize("kw,msg", [
+    (dict(M=-1), b"negative"),
+    (dict(N=-3), b"negative"),
+    (dict(M=2**31 - 1), b"int32"),
+    (dict(group=3), b"group_size"),
+    (dict(group=0), b"group_size"),
+    (dict(group=128), b"group_size"),
+    (dict(strategy=2), b"strategy"),
+    (dict(schedule=9), b"schedule"),
+    (dict(nnz_hint=-5), b"nnz_hint"),
+    (dict(rowptr=None), b"null"),
+    (dict(C=None), b"null"),
+    (dict(B=None), b"null"),
+])
+def test_invalid_arguments_are_rejected_without_launch(kw, msg):
+    lib = binding.load()
+    # fake non-null "device pointers": validation must fail before any use
+    a = dict(M=4, K=4, N=4, rowptr=0x1000, colidx=0x2000, vals=0x3000, B=0x4000, C=0x5000,
+             group=8, strategy=0, schedule=0, nnz_hint=-1)
+    a.update(kw)
+    rc = lib.sgap_spmm_csr_ex(a["M"], a["K"], a["N"], a["rowptr"], a["colidx"], a["vals"], a["B"], a["C"],
+                              a["group"], a["strategy"], a["schedule"], a["nnz_hint"], None)
+    assert rc == binding.SGAP_ERR_INVALID_ARG
+    assert msg in lib.sgap_last_error()
+
+
+def test_empty_shapes_are_ok_without_launch():
+    lib = binding.load()
+    assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0
+    assert lib.sgap_spmm_csr_ex(5, 5, 0, None, None, None, None, None, 8, 1, 1, -1, None) == 0
+    assert lib.sgap_spmm_csr(0, 0, 0, None, None, None, None, None, 64, 1, None) == 0
+
+
+def test_debug_entry_points_validate_layout():
+    lib = binding.load()
+    assert lib.sgap_debug_group_reduce(0x1000, 0x2000, 16, 8, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_debug_group_reduce(None, 0x2000, 4, 4, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_debug_group_seg_reduce(0x1000, 0x2000, 0x3000, 3, 1, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_copy_f32(0x1001, 0x2000, 4, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_copy_f32(None, None, 0, None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    t = torch.zeros(4)
+    with pytest.raises(TypeError):
+        binding.sgap_copy_f32(t, t)

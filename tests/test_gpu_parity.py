@@ -1,0 +1,266 @@
+"""GPU parity: every (group_size, strategy, schedule) point of the HIP path
+against the CPU oracle, through the C ABI, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_02882_amd import binding
+from paper_2209_02882_amd import workloads as wl
+
+from gpu_util import POINTS, DeviceProblem, assert_close, full_reference, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def ids(pt):
+    return f"g{pt[0]}-{pt[1]}-{pt[2]}"
+
+
+# ---------------------------------------------------------------- primitives
+
+def test_group_tree_sum_every_layout():
+    rng = np.random.default_rng(1)
+    for g in binding.GROUP_SIZES:
+        lc = 1
+        while g * lc <= 64:
+            x = rng.integers(-8, 9, size=64).astype(np.float32)  # exact in fp32
+            out = torch.full((64,), float("nan"), device="cuda:0")
+            binding.sgap_debug_group_reduce(torch.from_numpy(x).cuda(), out, g, lc)
+            got = out.cpu().numpy()
+            want = np.zeros(64, np.float32)
+            for lane in range(64):
+                member = (lane // lc) % g
+                if member == 0:
+                    want[lane] = sum(x[lane + m * lc] for m in range(g))
+            assert np.array_equal(got, want), f"group {g}, lanes per row {lc}"
+            lc *= 2
+
+
+def test_group_seg_sum_every_layout_and_random_runs():
+    rng = np.random.default_rng(2)
+    for g in binding.GROUP_SIZES:
+        lc = 1
+        while g * lc <= 64:
+            for trial in range(4):
+                x = rng.integers(-8, 9, size=64).astype(np.float32)
+                # random run boundaries per (slot, chunk): key changes with prob 0.4
+                span = np.zeros(64, np.int32)
+                want = np.zeros(64, np.float32)
+                for lane in range(64):
+                    chunk = lane % lc
+                    slot = lane // (g * lc)
+                    # runs are defined per slot, shared by its chunk lanes
+                    r = np.random.default_rng(1000 * trial + 64 * g + slot)
+                    cuts = r.random(g) < 0.4
+                    member = (lane // lc) % g
+                    s = 0
+                    while member + s + 1 < g and not cuts[member + s + 1]:
+                        s += 1
+                    span[lane] = s
+                    base = slot * g * lc + chunk
+                    want[lane] = sum(x[base + (member + j) * lc] for j in range(s + 1))
+                out = torch.full((64,), float("nan"), device="cuda:0")
+                binding.sgap_debug_group_seg_reduce(torch.from_numpy(x).cuda(), torch.from_numpy(span).cuda(),
+                                                    out, g, lc)
+                got = out.cpu().numpy()
+                # only the first lane of a run is used by the kernels, but every
+                # lane's value is defined; check them all
+                assert np.array_equal(got, want), f"group {g}, lanes per row {lc}, trial {trial}"
+            lc *= 2
+
+
+# ---------------------------------------------------- small named workloads
+
+@pytest.fixture(scope="module")
+def small_problems():
+    out = {}
+    for name, kw in [("uniform10", {}), ("uniform10_int", {}), ("powerlaw", {}),
+                     ("stencil27", dict(scale_down=64)), ("rmat", dict(scale_down=64)),
+                     ("skewed", dict(scale_down=25, N=64))]:
+        p = wl.make_problem(name, **kw)
+        out[name] = (DeviceProblem(p), full_reference(p))
+    return out
+
+
+@pytest.mark.parametrize("point", POINTS, ids=ids)
+@pytest.mark.parametrize("name", ["uniform10", "uniform10_int", "powerlaw", "stencil27", "rmat", "skewed"])
+def test_named_workloads_all_points(small_problems, name, point):
+    dp, (C_ref, BND) = small_problems[name]
+    C = dp.run(*point)
+    assert_close(C, C_ref, BND, exact=name.endswith("_int"), what=f"{name} {ids(point)}")
+
+
+def test_integer_variants_are_exact_everywhere():
+    # integer-valued copies of the irregular workloads: every order of
+    # summation gives the same fp32 number, so all points must agree exactly
+    for name, kw in [("powerlaw", dict(scale_down=4)), ("skewed", dict(scale_down=25, N=32))]:
+        p = wl.make_problem(name, **kw)
+        rng = np.random.default_rng(5)
+        p.vals = wl.fill_values(rng, p.nnz, True)
+        p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+        dp = DeviceProblem(p)
+        C_ref, BND = full_reference(p)
+        for point in POINTS:
+            assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"{name}-int {ids(point)}")
+
+
+def test_atomic_paths_repeat_within_tolerance():
+    p = wl.make_problem("powerlaw", scale_down=2)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for _ in range(5):
+        for point in [(8, "parallel", "nnz_balanced"), (32, "serial", "nnz_balanced")]:
+            assert_close(dp.run(*point), C_ref, BND, what=ids(point))
+
+
+# ---------------------------------------------------------------- edge cases
+
+def csr_problem(name, M, K, N, lengths, seed, integer=False):
+    rng = np.random.default_rng(seed)
+    rowptr, colidx = wl.csr_from_lengths(rng, np.asarray(lengths), K)
+    vals = wl.fill_values(rng, colidx.size, integer)
+    B = wl.fill_values(rng, K * N, integer).reshape(K, N)
+    return wl.SpmmProblem(name, M, K, N, rowptr, colidx, vals, B)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 6, 12, 20, 100, 130, 256, 260])
+def test_column_counts_and_vector_widths(N):
+    rng = np.random.default_rng(N)
+    M, K = 301, 257
+    lengths = rng.integers(0, 40, size=M)
+    p = csr_problem("cols", M, K, N, lengths, seed=N, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for point in POINTS:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"N={N} {ids(point)}")
+
+
+def test_empty_matrix_overwrites_with_zero():
+    M, K, N = 77, 50, 36
+    p = csr_problem("empty", M, K, N, np.zeros(M, np.int64), seed=1)
+    dp = DeviceProblem(p)
+    for point in POINTS:
+        C = dp.run(*point)
+        assert torch.equal(C, torch.zeros_like(C)), ids(point)
+        C = dp.run(*point, nnz_hint=-1)
+        assert torch.equal(C, torch.zeros_like(C)), ids(point)
+
+
+def test_identity_returns_B():
+    K, N = 1000, 32
+    p = wl.SpmmProblem("eye", K, K, N, np.arange(K + 1, dtype=np.int32), np.arange(K, dtype=np.int32),
+                       np.ones(K, np.float32), wl.dense_operand(3, K, N, False))
+    dp = DeviceProblem(p)
+    for point in POINTS:
+        C = dp.run(*point)
+        assert torch.equal(C, dp.B), ids(point)
+
+
+@pytest.mark.parametrize("lengths", [
+    [5000],                                  # one long row
+    [0, 0, 0, 3000, 0, 0],                   # long row between empty rows
+    [1] * 2048,                              # every row one entry
+    [64] * 64,                               # rows exactly one group wide
+    [63, 1, 64, 65, 0, 127, 128, 129],       # rows around group boundaries
+    [1023, 1, 1024, 1025, 0, 0, 2047, 1],    # rows around tile boundaries
+    [0] * 3000 + [7] + [0] * 3000 + [2000],  # many empty rows in a tile window
+    [2] * 512 + [0] * 5000 + [3] * 700,      # long empty stretch mid-matrix
+])
+def test_row_shapes_at_boundaries(lengths):
+    M = len(lengths)
+    p = csr_problem("shape", M, 6000, 8, lengths, seed=M, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for point in POINTS:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=ids(point))
+        assert_close(dp.run(*point, nnz_hint=-1), C_ref, BND, exact=True, what=ids(point) + " no hint")
+
+
+def test_unsorted_and_duplicate_columns():
+    rng = np.random.default_rng(12)
+    M, K, N = 200, 64, 16
+    lengths = rng.integers(0, 90, size=M)
+    rowptr = np.zeros(M + 1, np.int32)
+    rowptr[1:] = np.cumsum(lengths)
+    colidx = rng.integers(0, K, size=rowptr[-1]).astype(np.int32)  # unsorted, with repeats
+    p = wl.SpmmProblem("dups", M, K, N, rowptr, colidx, wl.fill_values(rng, colidx.size, True),
+                       wl.fill_values(rng, K * N, True).reshape(K, N))
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for point in POINTS:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=ids(point))
+
+
+def test_unaligned_operands_fall_back_to_narrow_vectors():
+    rng = np.random.default_rng(13)
+    M, K, N = 150, 90, 8
+    p = csr_problem("unaligned", M, K, N, rng.integers(0, 30, size=M), seed=13, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for off in (1, 2):  # 4-byte and 8-byte aligned views
+        Bbuf = torch.zeros(K * N + 4, device="cuda:0")
+        Cbuf = torch.full((M * N + 4,), float("nan"), device="cuda:0")
+        Bv = Bbuf[off:off + K * N]
+        Bv.copy_(dp.B.reshape(-1))
+        Cv = Cbuf[off:off + M * N]
+        for point in POINTS:
+            Cv.fill_(float("nan"))
+            binding.sgap_spmm_csr_ex(M, K, N, dp.rowptr, dp.colidx, dp.vals, Bv, Cv, point[0],
+                                     binding.STRATEGIES[point[1]], binding.SCHEDULES[point[2]])
+            torch.cuda.synchronize()
+            assert_close(Cv.reshape(M, N), C_ref, BND, exact=True, what=f"offset {off} {ids(point)}")
+        assert torch.isnan(Cbuf[:off]).all() and torch.isnan(Cbuf[off + M * N:]).all()
+
+
+def test_process_wide_schedule_entry_point():
+    p = wl.make_problem("uniform10_int")
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    try:
+        for sched in ("nnz_balanced", "row_split"):
+            binding.sgap_set_schedule(binding.SCHEDULES[sched])
+            for g in (1, 8, 64):
+                for st in ("parallel", "serial"):
+                    C = torch.full((p.M, p.N), float("nan"), device="cuda:0")
+                    binding.sgap_spmm_csr(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, g,
+                                          binding.STRATEGIES[st])
+                    torch.cuda.synchronize()
+                    assert_close(C, C_ref, BND, exact=True, what=f"{sched} g{g} {st}")
+    finally:
+        binding.sgap_set_schedule(binding.SGAP_SCHED_ROW_SPLIT)
+
+
+def test_runs_on_a_side_stream():
+    p = wl.make_problem("uniform10_int")
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    s = torch.cuda.Stream()
+    C = torch.full((p.M, p.N), float("nan"), device="cuda:0")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        binding.sgap_spmm_csr_ex(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, 8, 0, 1)
+    s.synchronize()
+    assert_close(C, C_ref, BND, exact=True)
+
+
+def test_profile_hooks_count_main_kernels():
+    p = wl.make_problem("uniform10")
+    dp = DeviceProblem(p)
+    binding.sgap_profile_enable(True)
+    try:
+        for _ in range(3):
+            dp.run(8, "parallel", "nnz_balanced", poison=False)
+        ms, n = binding.sgap_profile_collect()
+        assert n == 3 and ms > 0
+        assert binding.sgap_profile_collect() == (0.0, 0)
+    finally:
+        binding.sgap_profile_enable(False)
+
+
+def test_copy_kernel():
+    x = torch.arange(1003 * 4 + 3, dtype=torch.float32, device="cuda:0")
+    y = torch.zeros_like(x)
+    binding.sgap_copy_f32(x, y)
+    torch.cuda.synchronize()
+    assert torch.equal(x, y)
