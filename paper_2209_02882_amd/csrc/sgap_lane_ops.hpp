@@ -50,17 +50,18 @@ __device__ __forceinline__ float tree_step(float v)
     if constexpr (S <= 8) {
         return v + dpp_row_shl<S>(v);
     } else if constexpr (S == 16) {
-        // swaps 16-lane rows between the two operands (row 1 of the first
-        // with row 0 of the second, likewise rows 3 and 2); the two results
-        // added give v[i] + v[i^16] in every lane
-        auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v),
-                                                  __builtin_bit_cast(unsigned, v), false, false);
-        return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+        // v_permlane16_swap exchanges 16-lane rows between its two operands:
+        // with operands (v, 0) the results are [v.row0, 0, v.row2, 0] and
+        // [v.row1, 0, v.row3, 0]; their sum is v[i] + v[i+16] in rows 0 and 2.
+        auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), 0u, false, false);
+        const unsigned a = r[0], b = r[1];  // scalars first: bit_cast of a vector element misreads
+        return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
     } else {
         static_assert(S == 32, "wave64");
-        auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v),
-                                                  __builtin_bit_cast(unsigned, v), false, false);
-        return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+        // same with 32-lane halves: [v.lo, 0] and [v.hi, 0]
+        auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v), 0u, false, false);
+        const unsigned a = r[0], b = r[1];
+        return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
     }
 }
 
