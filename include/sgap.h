@@ -135,6 +135,25 @@ const char* sgap_last_error(void);
 int sgap_version(void);
 
 /*
+ * Tuning overrides in the spirit of the paper's Section 7.2 (tiling
+ * parameters are separate from the synchronisation granularity).  Process
+ * wide, not thread-safe; value 0 (or -1 where stated) restores the automatic
+ * choice.  They change speed only, never results beyond fp32 summation order.
+ *   SGAP_TUNE_TILE_COLS  columns of B/C per work item of the row-split
+ *                        schedule (rounded up to the vector width, capped at
+ *                        N); 0 = automatic.
+ *   SGAP_TUNE_XCD_REMAP  1/-1: hand each of the 8 dies a contiguous run of
+ *                        work items so that its L2 keeps the rows of B it
+ *                        gathers; 0: plain round-robin order.
+ *   SGAP_TUNE_ROWS_PER_GROUP  consecutive rows one group works through per
+ *                        work item in the row-split parallel strategy (the
+ *                        serial strategy takes group_size rows by definition);
+ *                        0 = automatic, from the mean row length.
+ */
+typedef enum { SGAP_TUNE_TILE_COLS = 0, SGAP_TUNE_XCD_REMAP = 1, SGAP_TUNE_ROWS_PER_GROUP = 2 } sgap_tuning_knob;
+int sgap_set_tuning(int knob, int value);
+
+/*
  * Timing hooks for benchmarks.  While enabled, every sgap_spmm_csr* call
  * brackets its main SpMM kernel (not the row-zeroing pass) with a pair of HIP
  * events on the call's stream.  sgap_profile_collect waits for those events,

@@ -37,6 +37,7 @@ EXPORTS = {
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
+    "sgap_set_tuning": (_int, [_int, _int]),
     "sgap_profile_enable": (_int, [_int]),
     "sgap_profile_collect": (_int, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_int)]),
     "sgap_debug_group_reduce": (_int, [_p, _p, _int, _int, _p]),
@@ -140,6 +141,15 @@ def sgap_spmm_csr_ex(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, 
         nnz_hint = colidx.numel()
     _check(load().sgap_spmm_csr_ex(M, K, N, *ptrs, int(group_size), int(strategy), int(schedule),
                                    int(nnz_hint), _stream_ptr(stream)))
+
+
+SGAP_TUNE_TILE_COLS = 0
+SGAP_TUNE_XCD_REMAP = 1
+SGAP_TUNE_ROWS_PER_GROUP = 2
+
+
+def sgap_set_tuning(knob: int, value: int) -> None:
+    _check(load().sgap_set_tuning(int(knob), int(value)))
 
 
 def sgap_profile_enable(on: bool) -> None:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsgap.so")
-SOURCES = ["sgap_api.hip", "sgap_row_split.hip", "sgap_nnz_balanced.hip"]
+SOURCES = ["sgap_api.hip", "sgap_row_split.hip", "sgap_nnz_parallel.hip", "sgap_nnz_serial.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU ops

@@ -91,6 +91,11 @@ namespace {
 int g_schedule = SGAP_SCHED_ROW_SPLIT;
 thread_local char t_last_error[256] = "";
 
+// tuning overrides; 0 = choose automatically
+int g_tile_cols = 0;
+int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
+int g_rows_per_slot = 0;
+
 bool g_profile = false;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
 
@@ -115,6 +120,9 @@ int pow2_ceil_capped(int64_t v, int cap)
     while (r < cap && r < v) r *= 2;
     return r;
 }
+
+constexpr int kXcds = 8;            // accelerator dies, each with its own L2
+constexpr int kAutoTileCols = 32;   // 128 bytes of a B row per work item
 
 int compute_units()
 {
@@ -169,33 +177,44 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     };
 
     if (schedule == SGAP_SCHED_ROW_SPLIT) {
+        // Column tile: how many columns of B/C one work item covers.  Narrow
+        // tiles keep the gathered rows of B inside one die's L2.
+        int64_t tile_cols = g_tile_cols > 0 ? g_tile_cols : kAutoTileCols;
+        if (tile_cols > N) tile_cols = N;
+        tile_cols = (tile_cols + vec - 1) / vec * vec;
+        const int64_t tile_chunks = tile_cols / vec;
+        const int xcds = g_xcd_remap == 0 ? 1 : kXcds;
+        const int cus = compute_units();
         if (strategy == SGAP_REDUCE_PARALLEL) {
-            const int lc = pow2_ceil_capped(chunks, 64 / group_size);
+            const int lc = pow2_ceil_capped(tile_chunks, 64 / group_size);
+            // rows a group works through per item: enough stored entries per
+            // workgroup to amortise staging (about one LDS chunk)
+            int rows_per_slot = g_rows_per_slot;
+            if (rows_per_slot <= 0) {
+                const int slots = 256 / (group_size * lc);
+                const double avg = nnz_hint > 0 ? (double)nnz_hint / (double)M : 16.0;
+                rows_per_slot = (int)(1536.0 / (avg * slots) + 0.5);
+                if (rows_per_slot < 1) rows_per_slot = 1;
+                if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
+            }
             mark(ev0);
-            err = launch_row_split_parallel(a, lc, vec, s);
+            err = launch_row_split(a, group_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus, s);
         } else {
-            const int lc = pow2_ceil_capped(chunks, 64);
+            const int lc = pow2_ceil_capped(tile_chunks, 64);
             mark(ev0);
-            err = launch_row_split_serial(a, lc, vec, s);
+            err = launch_row_split(a, 1, lc, vec, group_size, (int)tile_cols, xcds, cus, s);
         }
     } else {
-        // persistent grid: a few workgroups per compute unit, fewer if the
-        // caller told us A is small
-        int grid = compute_units() * 8;
-        if (nnz_hint >= 0) {
-            const int64_t tiles = (nnz_hint + 1023) / 1024;
-            if (tiles < grid) grid = tiles > 0 ? (int)tiles : 1;
-        }
         err = launch_nnz_zero_rows(a, vec, s);
         if (err == hipSuccess) {
             if (strategy == SGAP_REDUCE_PARALLEL) {
                 const int lc = pow2_ceil_capped(chunks, 64 / group_size);
                 mark(ev0);
-                err = launch_nnz_parallel(a, lc, vec, grid, s);
+                err = launch_nnz_parallel(a, lc, vec, compute_units(), nnz_hint, s);
             } else {
                 const int lc = pow2_ceil_capped(chunks, 64);
                 mark(ev0);
-                err = launch_nnz_serial(a, lc, vec, grid, s);
+                err = launch_nnz_serial(a, lc, vec, compute_units(), nnz_hint, s);
             }
         }
     }
@@ -248,6 +267,26 @@ const char* sgap_status_string(int status)
 const char* sgap_last_error(void) { return t_last_error; }
 
 int sgap_version(void) { return 100; }
+
+int sgap_set_tuning(int knob, int value)
+{
+    switch (knob) {
+        case SGAP_TUNE_TILE_COLS:
+            if (value < 0) return fail(SGAP_ERR_INVALID_ARG, "tile_cols must be >= 0");
+            g_tile_cols = value;
+            return SGAP_OK;
+        case SGAP_TUNE_XCD_REMAP:
+            if (value < -1 || value > 1) return fail(SGAP_ERR_INVALID_ARG, "xcd_remap must be -1, 0 or 1");
+            g_xcd_remap = value;
+            return SGAP_OK;
+        case SGAP_TUNE_ROWS_PER_GROUP:
+            if (value < 0 || value > 65536) return fail(SGAP_ERR_INVALID_ARG, "rows per group out of range");
+            g_rows_per_slot = value;
+            return SGAP_OK;
+        default:
+            return fail(SGAP_ERR_INVALID_ARG, "unknown tuning knob");
+    }
+}
 
 int sgap_profile_enable(int on)
 {

@@ -22,6 +22,22 @@ struct SpmmArgs {
     int group;        // group_size
 };
 
+// How the (row block x column tile) work items of a row-split launch are
+// laid over the grid.  The 8 accelerator dies (XCDs) of the chip each have a
+// private L2 and receive workgroups round-robin (workgroup b runs on XCD
+// b % 8), so item = (b % 8) * items_per_xcd + b / 8 hands every XCD one
+// contiguous run of the column-tile-major item order: one column tile and a
+// contiguous range of rows at a time, which keeps the rows of B it gathers
+// resident in its own L2.
+struct TileSched {
+    int64_t row_blocks;     // number of row blocks
+    int64_t items;          // row_blocks * col_tiles
+    int64_t items_per_xcd;  // ceil(items / xcds)
+    int32_t col_tiles;      // number of column tiles
+    int32_t tile_cols;      // columns per tile (multiple of VEC)
+    int32_t xcds;           // 8, or 1 to switch the remapping off
+};
+
 template <int VEC>
 struct Vec {
     float v[VEC];
@@ -66,6 +82,61 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const Vec<VEC>&
     }
 }
 
+// Streaming accesses: data touched once (A going in, C going out) should not
+// displace the rows of B that the L2 keeps for reuse.
+template <typename T>
+__device__ __forceinline__ T load_stream(const T* __restrict__ p)
+{
+    return __builtin_nontemporal_load(p);
+}
+
+typedef float native_f4 __attribute__((ext_vector_type(4)));
+typedef float native_f2 __attribute__((ext_vector_type(2)));
+
+template <int VEC>
+__device__ __forceinline__ void store_vec_stream(float* __restrict__ p, const Vec<VEC>& r)
+{
+    if constexpr (VEC == 4) {
+        native_f4 t = {r.v[0], r.v[1], r.v[2], r.v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<native_f4*>(p));
+    } else if constexpr (VEC == 2) {
+        native_f2 t = {r.v[0], r.v[1]};
+        __builtin_nontemporal_store(t, reinterpret_cast<native_f2*>(p));
+    } else {
+        __builtin_nontemporal_store(r.v[0], p);
+    }
+}
+
+// Address of B[col, k..): with OFF32 every byte offset into B fits 32 bits and
+// col, N*4 fit 24 bits, so one 24-bit multiply-add forms the offset and the
+// load uses the uniform base pointer plus a 32-bit lane offset.
+template <bool OFF32>
+struct BRow {
+    const char* __restrict__ base;  // B as bytes
+    uint32_t row_bytes;             // N * 4          (OFF32)
+    uint32_t k_bytes;               // k * 4          (OFF32)
+    int64_t N;                      // row stride     (!OFF32)
+    int64_t k;
+    __device__ __forceinline__ BRow(const float* B, int64_t n, int64_t k_)
+        : base(reinterpret_cast<const char*>(B)), row_bytes((uint32_t)(n * 4)), k_bytes((uint32_t)(k_ * 4)), N(n), k(k_)
+    {
+    }
+    __device__ __forceinline__ const float* at(int32_t col) const
+    {
+        if constexpr (OFF32) {
+            const uint32_t off = __umul24((uint32_t)col, row_bytes) + k_bytes;
+            return reinterpret_cast<const float*>(base + off);
+        } else {
+            return reinterpret_cast<const float*>(base) + ((int64_t)col * N + k);
+        }
+    }
+};
+
+inline bool offsets_fit_32(const SpmmArgs& a)
+{
+    return a.K <= (1 << 24) && a.N * 4 < (1 << 24) && a.K * a.N * 4 <= 0xffffffffLL;
+}
+
 // Cross-group merge: hardware fp32 atomic add (no return value needed).
 template <int VEC>
 __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<VEC>& r)
@@ -76,11 +147,15 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
 
 // ---- host-side launchers, one per kernel family (defined in the .hip files)
 // lc = chunk lanes per row (power of two), vec = columns per lane (1, 2, 4).
-hipError_t launch_row_split_parallel(const SpmmArgs& a, int lc, int vec, hipStream_t s);
-hipError_t launch_row_split_serial(const SpmmArgs& a, int lc, int vec, hipStream_t s);
+// g = lanes per row (1 for the serial strategy), rows_per_slot = consecutive
+// rows a group works through, tile_cols = columns per work item, xcds = 8 or
+// 1, compute_units = CUs of the device (sizes the persistent grid).
+hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, int tile_cols, int xcds,
+                            int compute_units, hipStream_t s);
 hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, hipStream_t s);
-hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int grid, hipStream_t s);
-hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int grid, hipStream_t s);
+// compute_units sizes the persistent grid; nnz_hint (-1 = unknown) caps it.
+hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
+hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
 hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);

@@ -1,0 +1,64 @@
+// The gather-multiply-accumulate inner loop shared by the schedules: stored
+// entries come from an LDS copy of colidx/vals, rows of B from memory.
+#pragma once
+#include "sgap_common.hpp"
+
+namespace sgap {
+
+// LDS copy of one stored entry of A
+struct StagedEntry {
+    int32_t col;
+    float val;
+};
+
+// Coalesced streaming copy of stored entries [base, base+cnt) into LDS.
+// The caller synchronises.
+__device__ __forceinline__ void stage_entries(const SpmmArgs& a, uint32_t base, uint32_t cnt,
+                                              StagedEntry* __restrict__ s_A)
+{
+    for (uint32_t q = threadIdx.x; q < cnt; q += kBlock) {
+        StagedEntry e;
+        e.col = load_stream(a.colidx + base + q);
+        e.val = load_stream(a.vals + base + q);
+        s_A[q] = e;
+    }
+}
+
+// U entries q, q+STRIDE, ... : all U rows of B are requested before the first
+// is consumed.
+template <int VEC, int STRIDE, bool OFF32, int U>
+__device__ __forceinline__ void gather_batch(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q,
+                                             const BRow<OFF32>& B)
+{
+    StagedEntry e[U];
+    Vec<VEC> b[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) e[j] = s_A[q + j * STRIDE];
+#pragma unroll
+    for (int j = 0; j < U; ++j) b[j] = load_vec<VEC>(B.at(e[j].col));
+#pragma unroll
+    for (int j = 0; j < U; ++j) acc.fma(e[j].val, b[j]);
+}
+
+// acc += sum over LDS slots q = q0, q0+STRIDE, ... < q1 of val[q] * B[col[q], k..k+VEC)
+// Full batches of 8, then the remainder as batches of 4, 2 and 1.
+template <int VEC, int STRIDE, bool OFF32>
+__device__ __forceinline__ void gather_fma(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q0,
+                                           uint32_t q1, const BRow<OFF32>& B)
+{
+    uint32_t q = q0;
+    for (; q + 7 * STRIDE < q1; q += 8 * STRIDE) gather_batch<VEC, STRIDE, OFF32, 8>(acc, s_A, q, B);
+    if (q >= q1) return;
+    const uint32_t left = (q1 - q + STRIDE - 1) / STRIDE;  // 1..7
+    if (left & 4) {
+        gather_batch<VEC, STRIDE, OFF32, 4>(acc, s_A, q, B);
+        q += 4 * STRIDE;
+    }
+    if (left & 2) {
+        gather_batch<VEC, STRIDE, OFF32, 2>(acc, s_A, q, B);
+        q += 2 * STRIDE;
+    }
+    if (left & 1) gather_batch<VEC, STRIDE, OFF32, 1>(acc, s_A, q, B);
+}
+
+}  // namespace sgap

@@ -3,144 +3,173 @@
 // produced by exactly one group (parallel strategy) or one lane (serial
 // strategy), so results are written with plain stores and empty rows are
 // written as zeros by their owner; no atomics, no zero-fill pass.
+//
+// One kernel template serves both strategies:
+//   parallel  {<1/g row, c col>, r}, g = r = G (Section 6.2, "1/g row"):
+//             the G members of a group share a row; member m takes the row's
+//             entries m, m+G, ... serially, the group tree-sums, member 0
+//             stores.  A group works through `rows_per_slot` consecutive rows
+//             (finite resource parallelism, Section 3.3).
+//   serial    {<g row, c col>, 1} (Section 6.1, "g row"): the same kernel with
+//             G = 1 and rows_per_slot = group_size.
+// Lane layout:  thread = (slot*G + member)*LC + chunk over the workgroup.
+//
+// Workgroups are persistent.  A work item is (block of consecutive rows,
+// column tile); the stored entries of a row block are contiguous in
+// colidx/vals, so the workgroup copies them (coalesced, streaming) into LDS in
+// chunks together with the block's slice of rowptr, and its lanes then read
+// (column, value) pairs from LDS: the vector memory path carries only the
+// gathered rows of B.
 #include "sgap_common.hpp"
+#include "sgap_gather.hpp"
 #include "sgap_lane_ops.hpp"
 
 namespace sgap {
 
-// {<1/g row, c col>, r} with g = r = G (Section 6.2, the "1/g row" listing):
-// G lanes share a row, lane `member` takes the row's entries member,
-// member+G, ... serially, then the group tree-sums and member 0 stores.
-//   lane = (slot*G + member)*LC + chunk ; one slot = one row
-template <int G, int LC, int VEC>
-__global__ __launch_bounds__(kBlock) void row_split_parallel_kernel(SpmmArgs a)
+constexpr int kStageCap = 2048;  // (column, value) pairs per LDS chunk: 16 KB
+constexpr int kRowCap = 1024;    // rowptr entries kept in LDS per row block (+1)
+
+template <int G, int LC, int VEC, bool OFF32>
+__global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot)
 {
+    __shared__ StagedEntry s_A[kStageCap];
+    __shared__ int32_t s_rp[kRowCap + 1];
     constexpr int SPAN = G * LC;
-    constexpr int ROWS_PER_WAVE = kWave / SPAN;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int slot = lane / SPAN;
-    const int member = (lane / LC) % G;
-    const int chunk = lane % LC;
+    constexpr int SLOTS = kBlock / SPAN;
 
-    const int64_t row = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * ROWS_PER_WAVE + slot;
-    const bool row_ok = row < a.M;
-    uint32_t p_begin = 0, p_end = 0;
-    if (row_ok) {
-        p_begin = (uint32_t)a.rowptr[row];
-        p_end = (uint32_t)a.rowptr[row + 1];
-    }
+    const int slot = threadIdx.x / SPAN;
+    const int member = (threadIdx.x / LC) % G;
+    const int chunk = threadIdx.x % LC;
     const int64_t N = a.N;
+    const int64_t rows_per_block = (int64_t)SLOTS * rows_per_slot;
+    const bool rp_in_lds = rows_per_block <= kRowCap;
 
-    // column tiles of LC*VEC columns; the trip count is uniform over the wave
-    for (int64_t k0 = 0; k0 < N; k0 += (int64_t)LC * VEC) {
-        const int64_t k = k0 + (int64_t)chunk * VEC;
-        const bool k_ok = k < N;
-        Vec<VEC> acc;
-        acc.zero();
-        if (k_ok) {
-            const float* __restrict__ Bk = a.B + k;
-            uint32_t p = p_begin + member;
-            // two entries in flight per lane
-            for (; p + G < p_end; p += 2 * G) {
-                const int32_t c0 = a.colidx[p];
-                const int32_t c1 = a.colidx[p + G];
-                const float v0 = a.vals[p];
-                const float v1 = a.vals[p + G];
-                const Vec<VEC> b0 = load_vec<VEC>(Bk + (int64_t)c0 * N);
-                const Vec<VEC> b1 = load_vec<VEC>(Bk + (int64_t)c1 * N);
-                acc.fma(v0, b0);
-                acc.fma(v1, b1);
-            }
-            if (p < p_end) {
-                const int32_t c0 = a.colidx[p];
-                const float v0 = a.vals[p];
-                acc.fma(v0, load_vec<VEC>(Bk + (int64_t)c0 * N));
-            }
+    // persistent walk over this die's run of work items
+    const int64_t xcd = blockIdx.x % ts.xcds;
+    const int64_t wg_in_xcd = blockIdx.x / ts.xcds;
+    const int64_t wgs_per_xcd = gridDim.x / ts.xcds;
+    for (int64_t it = wg_in_xcd; it < ts.items_per_xcd; it += wgs_per_xcd) {
+        const int64_t item = xcd * ts.items_per_xcd + it;
+        if (item >= ts.items) break;
+        const int32_t col_tile = (int32_t)(item / ts.row_blocks);
+        const int64_t row_block = item % ts.row_blocks;
+
+        const int64_t row_first = row_block * rows_per_block;
+        const int64_t row_last = row_first + rows_per_block < a.M ? row_first + rows_per_block : a.M;
+        int64_t my_first = row_first + (int64_t)slot * rows_per_slot;
+        int64_t my_last = my_first + rows_per_slot;
+        if (my_first > row_last) my_first = row_last;
+        if (my_last > row_last) my_last = row_last;
+
+        __syncthreads();  // everyone is done with the previous item's LDS contents
+        if (rp_in_lds) {
+            for (int i = threadIdx.x; i <= (int)(row_last - row_first); i += kBlock)
+                s_rp[i] = a.rowptr[row_first + i];
+            __syncthreads();
         }
-        // lanes without work contributed +0 (zero extension); all lanes reduce
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
-        if (member == 0 && row_ok && k_ok) store_vec<VEC>(a.C + row * N + k, acc);
-    }
-}
+        const uint32_t nz_first = (uint32_t)a.rowptr[row_first];
+        const uint32_t nz_last = (uint32_t)a.rowptr[row_last];
 
-// {<g row, c col>, 1} (Section 6.1, the "g row" listing): reduction
-// parallelism 1.  A lane owns `group` consecutive rows for its column chunk
-// and walks each row serially.
-//   lane = row_lane*LC + chunk
-template <int LC, int VEC>
-__global__ __launch_bounds__(kBlock) void row_split_serial_kernel(SpmmArgs a)
-{
-    constexpr int ROW_LANES = kWave / LC;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int row_lane = lane / LC;
-    const int chunk = lane % LC;
-    const int64_t N = a.N;
-    const int64_t row0 = (((int64_t)blockIdx.x * kWavesPerBlock + wave) * ROW_LANES + row_lane) * a.group;
-    const int64_t row1 = row0 + a.group < a.M ? row0 + a.group : a.M;
+        const int64_t k_tile_end =
+            (int64_t)(col_tile + 1) * ts.tile_cols < N ? (int64_t)(col_tile + 1) * ts.tile_cols : N;
+        // a tile may be wider than one pass of the LC chunk lanes
+        for (int64_t k0 = (int64_t)col_tile * ts.tile_cols; k0 < k_tile_end; k0 += (int64_t)LC * VEC) {
+            const int64_t k = k0 + (int64_t)chunk * VEC;
+            const bool k_ok = k < k_tile_end;
+            const BRow<OFF32> Brow(a.B, N, k);
 
-    for (int64_t k0 = 0; k0 < N; k0 += (int64_t)LC * VEC) {
-        const int64_t k = k0 + (int64_t)chunk * VEC;
-        if (k >= N) continue;
-        const float* __restrict__ Bk = a.B + k;
-        for (int64_t row = row0; row < row1; ++row) {
-            uint32_t p = (uint32_t)a.rowptr[row];
-            const uint32_t p_end = (uint32_t)a.rowptr[row + 1];
+            int64_t row = my_first;
             Vec<VEC> acc;
             acc.zero();
-            for (; p + 1 < p_end; p += 2) {
-                const int32_t c0 = a.colidx[p];
-                const int32_t c1 = a.colidx[p + 1];
-                const float v0 = a.vals[p];
-                const float v1 = a.vals[p + 1];
-                const Vec<VEC> b0 = load_vec<VEC>(Bk + (int64_t)c0 * N);
-                const Vec<VEC> b1 = load_vec<VEC>(Bk + (int64_t)c1 * N);
-                acc.fma(v0, b0);
-                acc.fma(v1, b1);
+            for (uint32_t base = nz_first;; base += kStageCap) {  // runs at least once: empty rows get stored
+                const uint32_t cnt = nz_last - base < (uint32_t)kStageCap ? nz_last - base : (uint32_t)kStageCap;
+                if (base != nz_first || k0 != (int64_t)col_tile * ts.tile_cols) __syncthreads();
+                stage_entries(a, base, cnt, s_A);
+                __syncthreads();
+                // rows of this slot that have entries in the chunk (or are empty)
+                while (row < my_last) {
+                    uint32_t p_begin, p_end;
+                    if (rp_in_lds) {
+                        p_begin = (uint32_t)s_rp[row - row_first];
+                        p_end = (uint32_t)s_rp[row - row_first + 1];
+                    } else {
+                        p_begin = (uint32_t)a.rowptr[row];
+                        p_end = (uint32_t)a.rowptr[row + 1];
+                    }
+                    const uint32_t lo = p_begin > base ? p_begin : base;
+                    const uint32_t hi = p_end < base + cnt ? p_end : base + cnt;
+                    if (k_ok && lo < hi) {
+                        // first position >= lo that belongs to this member
+                        const uint32_t first = lo + ((member - (lo - p_begin)) & (G - 1));
+                        if (first < hi) gather_fma<VEC, G, OFF32>(acc, s_A, first - base, hi - base, Brow);
+                    }
+                    if (p_end > base + cnt) break;  // the row continues in the next chunk
+                    // members without entries contributed +0 (zero extension);
+                    // the lanes of a slot reach this point together
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
+                    if (member == 0 && k_ok) store_vec_stream<VEC>(a.C + row * N + k, acc);
+                    acc.zero();
+                    ++row;
+                }
+                if (base + cnt >= nz_last) break;
             }
-            if (p < p_end) acc.fma(a.vals[p], load_vec<VEC>(Bk + (int64_t)a.colidx[p] * N));
-            store_vec<VEC>(a.C + row * N + k, acc);
         }
     }
 }
 
 namespace {
-struct LaunchRowSplitParallel {
+
+struct LaunchRowSplit {
     const SpmmArgs& a;
+    int rows_per_slot, tile_cols, xcds, compute_units;
+    bool off32;
     hipStream_t s;
+
+    // workgroups of this instance that one compute unit can hold at once
+    template <typename K>
+    static int resident_per_cu(K kernel)
+    {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n < 1) n = 1;
+        return n;
+    }
+
     template <int G, int LC, int VEC>
     void operator()() const
     {
-        constexpr int rows_per_block = kWavesPerBlock * (kWave / (G * LC));
-        const int64_t grid = (a.M + rows_per_block - 1) / rows_per_block;
-        hipLaunchKernelGGL((row_split_parallel_kernel<G, LC, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+        // a persistent grid must be resident all at once
+        static const int per_cu_32 = resident_per_cu(row_split_kernel<G, LC, VEC, true>);
+        static const int per_cu_64 = resident_per_cu(row_split_kernel<G, LC, VEC, false>);
+        const int max_grid = compute_units * (off32 ? per_cu_32 : per_cu_64);
+        constexpr int slots = kBlock / (G * LC);
+        const int64_t rows_per_block = (int64_t)slots * rows_per_slot;
+        TileSched ts;
+        ts.row_blocks = (a.M + rows_per_block - 1) / rows_per_block;
+        ts.tile_cols = tile_cols;
+        ts.col_tiles = (int32_t)((a.N + tile_cols - 1) / tile_cols);
+        ts.items = ts.row_blocks * ts.col_tiles;
+        ts.xcds = xcds;
+        ts.items_per_xcd = (ts.items + xcds - 1) / xcds;
+        int64_t wgs_per_xcd = max_grid / xcds > 0 ? max_grid / xcds : 1;
+        if (wgs_per_xcd > ts.items_per_xcd) wgs_per_xcd = ts.items_per_xcd;
+        const unsigned grid = (unsigned)(wgs_per_xcd * xcds);
+        if (off32)
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true>), dim3(grid), dim3(kBlock), 0, s, a, ts,
+                               rows_per_slot);
+        else
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false>), dim3(grid), dim3(kBlock), 0, s, a, ts,
+                               rows_per_slot);
     }
 };
-struct LaunchRowSplitSerial {
-    const SpmmArgs& a;
-    hipStream_t s;
-    template <int G, int LC, int VEC>
-    void operator()() const
-    {
-        const int64_t rows_per_block = (int64_t)kWavesPerBlock * (kWave / LC) * a.group;
-        const int64_t grid = (a.M + rows_per_block - 1) / rows_per_block;
-        hipLaunchKernelGGL((row_split_serial_kernel<LC, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
-    }
-};
+
 }  // namespace
 
-hipError_t launch_row_split_parallel(const SpmmArgs& a, int lc, int vec, hipStream_t s)
+hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, int tile_cols, int xcds,
+                            int compute_units, hipStream_t s)
 {
-    if (!dispatch_group(a.group, lc, vec, LaunchRowSplitParallel{a, s})) return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-hipError_t launch_row_split_serial(const SpmmArgs& a, int lc, int vec, hipStream_t s)
-{
-    // group is a run-time loop count here; dispatch on (lc, vec) only
-    if (!dispatch_lc<1>(lc, vec, LaunchRowSplitSerial{a, s})) return hipErrorInvalidValue;
+    LaunchRowSplit f{a, rows_per_slot, tile_cols, xcds, compute_units, offsets_fit_32(a), s};
+    if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
