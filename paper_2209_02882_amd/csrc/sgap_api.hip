@@ -205,17 +205,14 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
             err = launch_row_split(a, 1, lc, vec, group_size, (int)tile_cols, xcds, cus, s);
         }
     } else {
-        err = launch_nnz_zero_rows(a, vec, s);
+        const bool par = strategy == SGAP_REDUCE_PARALLEL;
+        const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);
+        const NnzPlan plan = par ? plan_nnz_parallel(group_size, lc, vec) : plan_nnz_serial(group_size, lc, vec);
+        err = launch_nnz_zero_rows(a, vec, plan.merge_log2, s);
         if (err == hipSuccess) {
-            if (strategy == SGAP_REDUCE_PARALLEL) {
-                const int lc = pow2_ceil_capped(chunks, 64 / group_size);
-                mark(ev0);
-                err = launch_nnz_parallel(a, lc, vec, compute_units(), nnz_hint, s);
-            } else {
-                const int lc = pow2_ceil_capped(chunks, 64);
-                mark(ev0);
-                err = launch_nnz_serial(a, lc, vec, compute_units(), nnz_hint, s);
-            }
+            mark(ev0);
+            err = par ? launch_nnz_parallel(a, lc, vec, compute_units(), nnz_hint, s)
+                      : launch_nnz_serial(a, lc, vec, compute_units(), nnz_hint, s);
         }
     }
     if (ev0) {

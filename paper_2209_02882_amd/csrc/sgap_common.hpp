@@ -152,7 +152,17 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
 // 1, compute_units = CUs of the device (sizes the persistent grid).
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, int tile_cols, int xcds,
                             int compute_units, hipStream_t s);
-hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, hipStream_t s);
+// How an nnz-balanced kernel cuts the stored entries: tile = positions per LDS
+// tile, merge = tile mode of the merge rule, merge_log2 = log2 of the merge
+// block the zeroing pass must assume (tile in tile mode, group otherwise).
+struct NnzPlan {
+    int tile;
+    bool merge;
+    int merge_log2;
+};
+NnzPlan plan_nnz_serial(int group, int lc, int vec);
+NnzPlan plan_nnz_parallel(int group, int lc, int vec);
+hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, int merge_log2, hipStream_t s);
 // compute_units sizes the persistent grid; nnz_hint (-1 = unknown) caps it.
 hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
 hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);

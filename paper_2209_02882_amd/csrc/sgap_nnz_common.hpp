@@ -2,10 +2,17 @@
 // entries, finding the rows a tile touches, and the write-back rule.
 //
 // Merge rule (both strategies and the zeroing pass): positions are grouped in
-// aligned blocks of `group` positions.  A non-empty row whose positions all
-// fall in one block is produced by exactly one writer and is stored plainly;
-// every other row is zeroed by zero_rows_kernel beforehand and receives
-// partial sums through fp32 atomic adds.
+// aligned "merge blocks" of 2^merge_log2 positions.  A non-empty row whose
+// positions all fall in one merge block is written exactly once with a plain
+// store; every other row is zeroed by zero_rows_kernel beforehand and receives
+// partial sums through global fp32 atomic adds.
+//   direct mode: merge block = the `group` positions of one segment group /
+//     lane; every partial sum of a group goes straight to global memory.
+//   tile mode:   merge block = one tile of positions.  Partial sums of rows
+//     that lie inside the tile are first combined in LDS accumulators (LDS
+//     atomic adds) and written once; only rows that cross a tile boundary use
+//     global atomics.  Global fp32 atomics are far more expensive than loads
+//     on this chip, so tile mode is used whenever the accumulators fit.
 #pragma once
 #include "sgap_common.hpp"
 
@@ -77,19 +84,31 @@ __device__ __forceinline__ RowWindow load_row_window(const SpmmArgs& a, int32_t&
     return w;
 }
 
-// Stored entries are handed to workgroups in contiguous runs of whole tiles,
-// so that each workgroup walks rowptr forward only once.
-struct PosRange { int64_t begin, end; };
-__device__ __forceinline__ PosRange my_positions(int32_t nnz, int tile)
+// Tiles are dealt to the persistent workgroups round-robin (workgroup b takes
+// tiles b, b + grid, ...), so that every workgroup gets its share of cheap and
+// of expensive stretches of A (long rows vs. many short or empty rows).  The
+// row of a tile's first position is found by the whole workgroup together:
+// each round probes rowptr at up to kBlock evenly spaced rows and keeps the
+// stretch between the last probe at or before `pos` and the next one.
+// Returns the largest r in [lo, hi] with rowptr[r] <= pos (rowptr[lo] <= pos
+// is given).  Block-uniform; contains barriers.
+__device__ __forceinline__ int32_t find_row_cooperative(const int32_t* __restrict__ rowptr, int32_t lo, int32_t hi,
+                                                        int32_t pos)
 {
-    const int64_t tiles = ((int64_t)nnz + tile - 1) / tile;
-    const int64_t per = (tiles + gridDim.x - 1) / gridDim.x;
-    PosRange r;
-    r.begin = (int64_t)blockIdx.x * per * tile;
-    r.end = r.begin + per * tile;
-    if (r.begin > nnz) r.begin = nnz;
-    if (r.end > nnz) r.end = nnz;
-    return r;
+    const int tid = threadIdx.x;
+    while (lo < hi) {
+        const int64_t span = (int64_t)hi - lo;
+        const int64_t step = (span + kBlock - 1) / kBlock;  // >= 1
+        int64_t r = (int64_t)lo + (tid + 1) * step;
+        if (r > hi) r = hi;
+        const int cnt = __syncthreads_count(rowptr[r] <= pos);  // probes are sorted: the first cnt hold
+        if (cnt == kBlock) return hi;  // the last probe is hi itself
+        int64_t next = (int64_t)lo + (cnt + 1) * step;  // first probe beyond pos
+        if (next > hi) next = hi;
+        if (cnt > 0) lo = (int32_t)((int64_t)lo + cnt * step);
+        hi = (int32_t)next - 1;
+    }
+    return lo;
 }
 
 template <int VEC>
@@ -98,6 +117,70 @@ __device__ __forceinline__ void write_out(const SpmmArgs& a, int32_t row, int64_
 {
     float* __restrict__ dst = a.C + (int64_t)row * a.N + k;
     if (plain) store_vec<VEC>(dst, x); else atomic_add_vec<VEC>(dst, x);
+}
+
+// LDS accumulators of tile mode.  Slot s < nslots-1 belongs to the row whose
+// first stored entry lies in the s-th aligned block of `group` positions of
+// the tile and which continues past that block (at most one such row per
+// block); the last slot belongs to the row that entered the chunk from the
+// left.  Each slot holds `width` floats: the columns of the current pass.
+struct MergeBuf {
+    float* accum;          // nslots * width floats, zero between uses
+    int32_t* slot_row;     // nslots, -1 = unused
+    int32_t* slot_atomic;  // nslots, 1 = the row also has entries outside the chunk
+    int32_t nslots;
+    int32_t width;
+};
+
+__device__ __forceinline__ void merge_reset(const MergeBuf& mb)
+{
+    for (int i = threadIdx.x; i < mb.nslots * mb.width; i += kBlock) mb.accum[i] = 0.0f;
+    for (int i = threadIdx.x; i < mb.nslots; i += kBlock) mb.slot_row[i] = -1;
+}
+
+// One lane adds its partial sum of a row into the row's slot.  `owner` is set
+// for the lane that holds the row's first entry inside the chunk (column
+// chunk 0 only): it records which row the slot stands for.
+template <int VEC>
+__device__ __forceinline__ void merge_add(const MergeBuf& mb, int32_t slot, int lane_col, const Vec<VEC>& x,
+                                          bool owner, int32_t row, bool needs_atomic)
+{
+    float* dst = mb.accum + slot * mb.width + lane_col;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+        __hip_atomic_fetch_add(dst + i, x.v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (owner) {
+        mb.slot_row[slot] = row;
+        mb.slot_atomic[slot] = needs_atomic ? 1 : 0;
+    }
+}
+
+// After a barrier: write every used slot to C (plain store, or global atomic
+// add for rows that continue outside the chunk) and clear it for the next use.
+// thread = slot_lane*LC + chunk, the same column mapping as the compute phase.
+// The LC lanes of a slot sit in one wavefront, so the owner lane's reset of
+// slot_row cannot overtake the other lanes' reads.
+template <int LC, int VEC>
+__device__ __forceinline__ void merge_write_out(const SpmmArgs& a, const MergeBuf& mb, int64_t k, bool k_ok)
+{
+    constexpr int SLOT_LANES = kBlock / LC;
+    const int chunk = threadIdx.x % LC;
+    for (int s = threadIdx.x / LC; s < mb.nslots; s += SLOT_LANES) {
+        const int32_t row = mb.slot_row[s];
+        if (row < 0) continue;
+        float* src = mb.accum + s * mb.width + chunk * VEC;
+        Vec<VEC> x;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            x.v[i] = src[i];
+            src[i] = 0.0f;
+        }
+        if (k_ok) {
+            float* __restrict__ dst = a.C + (int64_t)row * a.N + k;
+            if (mb.slot_atomic[s]) atomic_add_vec<VEC>(dst, x); else store_vec_stream<VEC>(dst, x);
+        }
+        if (chunk == 0) mb.slot_row[s] = -1;
+    }
 }
 
 // Host side: workgroups of a kernel instance one compute unit can hold, and
