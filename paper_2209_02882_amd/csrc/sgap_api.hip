@@ -122,7 +122,7 @@ int pow2_ceil_capped(int64_t v, int cap)
 }
 
 constexpr int kXcds = 8;            // accelerator dies, each with its own L2
-constexpr int kAutoTileCols = 32;   // 128 bytes of a B row per work item
+constexpr int kAutoTileCols = 128;  // 512 bytes of a B row per work item
 
 int compute_units()
 {
