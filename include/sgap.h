@@ -145,7 +145,7 @@ int sgap_version(void);
  *   SGAP_TUNE_XCD_REMAP  1/-1: hand each of the 8 dies a contiguous run of
  *                        work items so that its L2 keeps the rows of B it
  *                        gathers; 0: plain round-robin order.
- *   SGAP_TUNE_ROWS_PER_GROUP  consecutive rows one group works through per
+ *   SGAP_TUNE_ROWS_PER_GROUP  rows one group works through per
  *                        work item in the row-split parallel strategy (the
  *                        serial strategy takes group_size rows by definition);
  *                        0 = automatic, from the mean row length.

@@ -177,33 +177,29 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     };
 
     if (schedule == SGAP_SCHED_ROW_SPLIT) {
-        // Column tile: how many columns of B/C one work item covers.  Narrow
-        // tiles keep the gathered rows of B inside one die's L2.
+        const int xcds = g_xcd_remap == 0 ? 1 : kXcds;
+        const int cus = compute_units();
+        const bool par = strategy == SGAP_REDUCE_PARALLEL;
+        const int g = par ? group_size : 1;  // lanes per row
+        const double avg_row = nnz_hint > 0 ? (double)nnz_hint / (double)M : 16.0;
+        // Column tile: how many columns of B/C one work item covers.
         int64_t tile_cols = g_tile_cols > 0 ? g_tile_cols : kAutoTileCols;
         if (tile_cols > N) tile_cols = N;
         tile_cols = (tile_cols + vec - 1) / vec * vec;
-        const int64_t tile_chunks = tile_cols / vec;
-        const int xcds = g_xcd_remap == 0 ? 1 : kXcds;
-        const int cus = compute_units();
-        if (strategy == SGAP_REDUCE_PARALLEL) {
-            const int lc = pow2_ceil_capped(tile_chunks, 64 / group_size);
+        const int lc = pow2_ceil_capped(tile_cols / vec, 64 / g);
+        int rows_per_slot = par ? g_rows_per_slot : group_size;
+        if (rows_per_slot <= 0) {
             // rows a group works through per item: enough stored entries per
             // workgroup to amortise staging (about one LDS chunk)
-            int rows_per_slot = g_rows_per_slot;
-            if (rows_per_slot <= 0) {
-                const int slots = 256 / (group_size * lc);
-                const double avg = nnz_hint > 0 ? (double)nnz_hint / (double)M : 16.0;
-                rows_per_slot = (int)(1536.0 / (avg * slots) + 0.5);
-                if (rows_per_slot < 1) rows_per_slot = 1;
-                if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
-            }
-            mark(ev0);
-            err = launch_row_split(a, group_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus, s);
-        } else {
-            const int lc = pow2_ceil_capped(tile_chunks, 64);
-            mark(ev0);
-            err = launch_row_split(a, 1, lc, vec, group_size, (int)tile_cols, xcds, cus, s);
+            const int slots = 256 / (g * lc);
+            rows_per_slot = (int)(1536.0 / (avg_row * slots) + 0.5);
+            if (rows_per_slot < 1) rows_per_slot = 1;
+            if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
         }
+        mark(ev0);
+        // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
+        // own consecutive rows by definition
+        err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, s);
     } else {
         const bool par = strategy == SGAP_REDUCE_PARALLEL;
         const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);

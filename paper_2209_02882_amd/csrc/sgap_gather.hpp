@@ -24,41 +24,50 @@ __device__ __forceinline__ void stage_entries(const SpmmArgs& a, uint32_t base, 
     }
 }
 
+// Where the rows of B come from: the `col` field of a staged entry is the key
+// handed to load().
+template <int VEC, bool OFF32>
+struct GlobalRows {
+    BRow<OFF32> b;
+    __device__ __forceinline__ GlobalRows(const float* B, int64_t n, int64_t k) : b(B, n, k) {}
+    __device__ __forceinline__ Vec<VEC> load(int32_t col) const { return load_vec<VEC>(b.at(col)); }
+};
+
 // U entries q, q+STRIDE, ... : all U rows of B are requested before the first
 // is consumed.
-template <int VEC, int STRIDE, bool OFF32, int U>
+template <int VEC, int STRIDE, int U, typename SRC>
 __device__ __forceinline__ void gather_batch(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q,
-                                             const BRow<OFF32>& B)
+                                             const SRC& B)
 {
     StagedEntry e[U];
     Vec<VEC> b[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) e[j] = s_A[q + j * STRIDE];
 #pragma unroll
-    for (int j = 0; j < U; ++j) b[j] = load_vec<VEC>(B.at(e[j].col));
+    for (int j = 0; j < U; ++j) b[j] = B.load(e[j].col);
 #pragma unroll
     for (int j = 0; j < U; ++j) acc.fma(e[j].val, b[j]);
 }
 
 // acc += sum over LDS slots q = q0, q0+STRIDE, ... < q1 of val[q] * B[col[q], k..k+VEC)
 // Full batches of 8, then the remainder as batches of 4, 2 and 1.
-template <int VEC, int STRIDE, bool OFF32>
+template <int VEC, int STRIDE, typename SRC>
 __device__ __forceinline__ void gather_fma(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q0,
-                                           uint32_t q1, const BRow<OFF32>& B)
+                                           uint32_t q1, const SRC& B)
 {
     uint32_t q = q0;
-    for (; q + 7 * STRIDE < q1; q += 8 * STRIDE) gather_batch<VEC, STRIDE, OFF32, 8>(acc, s_A, q, B);
+    for (; q + 7 * STRIDE < q1; q += 8 * STRIDE) gather_batch<VEC, STRIDE, 8>(acc, s_A, q, B);
     if (q >= q1) return;
     const uint32_t left = (q1 - q + STRIDE - 1) / STRIDE;  // 1..7
     if (left & 4) {
-        gather_batch<VEC, STRIDE, OFF32, 4>(acc, s_A, q, B);
+        gather_batch<VEC, STRIDE, 4>(acc, s_A, q, B);
         q += 4 * STRIDE;
     }
     if (left & 2) {
-        gather_batch<VEC, STRIDE, OFF32, 2>(acc, s_A, q, B);
+        gather_batch<VEC, STRIDE, 2>(acc, s_A, q, B);
         q += 2 * STRIDE;
     }
-    if (left & 1) gather_batch<VEC, STRIDE, OFF32, 1>(acc, s_A, q, B);
+    if (left & 1) gather_batch<VEC, STRIDE, 1>(acc, s_A, q, B);
 }
 
 }  // namespace sgap

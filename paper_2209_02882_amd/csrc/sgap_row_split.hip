@@ -8,8 +8,10 @@
 //   parallel  {<1/g row, c col>, r}, g = r = G (Section 6.2, "1/g row"):
 //             the G members of a group share a row; member m takes the row's
 //             entries m, m+G, ... serially, the group tree-sums, member 0
-//             stores.  A group works through `rows_per_slot` consecutive rows
-//             (finite resource parallelism, Section 3.3).
+//             stores.  A group works through `rows_per_slot` rows of its row
+//             block (finite resource parallelism, Section 3.3), interleaved
+//             with the other groups' rows so that neighbouring rows, which
+//             tend to share columns, are in flight together.
 //   serial    {<g row, c col>, 1} (Section 6.1, "g row"): the same kernel with
 //             G = 1 and rows_per_slot = group_size.
 // Lane layout:  thread = (slot*G + member)*LC + chunk over the workgroup.
@@ -30,7 +32,8 @@ constexpr int kStageCap = 2048;  // (column, value) pairs per LDS chunk: 16 KB
 constexpr int kRowCap = 1024;    // rowptr entries kept in LDS per row block (+1)
 
 template <int G, int LC, int VEC, bool OFF32>
-__global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot)
+__global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot,
+                                                           int interleave)
 {
     __shared__ StagedEntry s_A[kStageCap];
     __shared__ int32_t s_rp[kRowCap + 1];
@@ -56,8 +59,10 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
 
         const int64_t row_first = row_block * rows_per_block;
         const int64_t row_last = row_first + rows_per_block < a.M ? row_first + rows_per_block : a.M;
-        int64_t my_first = row_first + (int64_t)slot * rows_per_slot;
-        int64_t my_last = my_first + rows_per_slot;
+        // this slot's rows: my_first, my_first + row_step, ... below my_last
+        const int64_t row_step = interleave ? SLOTS : 1;
+        int64_t my_first = row_first + (interleave ? (int64_t)slot : (int64_t)slot * rows_per_slot);
+        int64_t my_last = interleave ? row_last : my_first + rows_per_slot;
         if (my_first > row_last) my_first = row_last;
         if (my_last > row_last) my_last = row_last;
 
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
         for (int64_t k0 = (int64_t)col_tile * ts.tile_cols; k0 < k_tile_end; k0 += (int64_t)LC * VEC) {
             const int64_t k = k0 + (int64_t)chunk * VEC;
             const bool k_ok = k < k_tile_end;
-            const BRow<OFF32> Brow(a.B, N, k);
+            const GlobalRows<VEC, OFF32> Brow(a.B, N, k);
 
             int64_t row = my_first;
             Vec<VEC> acc;
@@ -101,7 +106,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                     if (k_ok && lo < hi) {
                         // first position >= lo that belongs to this member
                         const uint32_t first = lo + ((member - (lo - p_begin)) & (G - 1));
-                        if (first < hi) gather_fma<VEC, G, OFF32>(acc, s_A, first - base, hi - base, Brow);
+                        if (first < hi) gather_fma<VEC, G>(acc, s_A, first - base, hi - base, Brow);
                     }
                     if (p_end > base + cnt) break;  // the row continues in the next chunk
                     // members without entries contributed +0 (zero extension);
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                     for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
                     if (member == 0 && k_ok) store_vec_stream<VEC>(a.C + row * N + k, acc);
                     acc.zero();
-                    ++row;
+                    row += row_step;
                 }
                 if (base + cnt >= nz_last) break;
             }
@@ -122,7 +127,7 @@ namespace {
 
 struct LaunchRowSplit {
     const SpmmArgs& a;
-    int rows_per_slot, tile_cols, xcds, compute_units;
+    int rows_per_slot, interleave, tile_cols, xcds, compute_units;
     bool off32;
     hipStream_t s;
 
@@ -156,19 +161,19 @@ struct LaunchRowSplit {
         const unsigned grid = (unsigned)(wgs_per_xcd * xcds);
         if (off32)
             hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true>), dim3(grid), dim3(kBlock), 0, s, a, ts,
-                               rows_per_slot);
+                               rows_per_slot, interleave);
         else
             hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false>), dim3(grid), dim3(kBlock), 0, s, a, ts,
-                               rows_per_slot);
+                               rows_per_slot, interleave);
     }
 };
 
 }  // namespace
 
-hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, int tile_cols, int xcds,
-                            int compute_units, hipStream_t s)
+hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
+                            int tile_cols, int xcds, int compute_units, hipStream_t s)
 {
-    LaunchRowSplit f{a, rows_per_slot, tile_cols, xcds, compute_units, offsets_fit_32(a), s};
+    LaunchRowSplit f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units, offsets_fit_32(a), s};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }
