@@ -150,7 +150,7 @@ int sgap_version(void);
  *                        serial strategy takes group_size rows by definition);
  *                        0 = automatic, from the mean row length.
  */
-typedef enum { SGAP_TUNE_TILE_COLS = 0, SGAP_TUNE_XCD_REMAP = 1, SGAP_TUNE_ROWS_PER_GROUP = 2 } sgap_tuning_knob;
+typedef enum { SGAP_TUNE_TILE_COLS = 0, SGAP_TUNE_XCD_REMAP = 1, SGAP_TUNE_ROWS_PER_GROUP = 2, SGAP_TUNE_PERSISTENT = 3 } sgap_tuning_knob;
 int sgap_set_tuning(int knob, int value);
 
 /*

@@ -146,6 +146,7 @@ def sgap_spmm_csr_ex(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, 
 SGAP_TUNE_TILE_COLS = 0
 SGAP_TUNE_XCD_REMAP = 1
 SGAP_TUNE_ROWS_PER_GROUP = 2
+SGAP_TUNE_PERSISTENT = 3
 
 
 def sgap_set_tuning(knob: int, value: int) -> None:

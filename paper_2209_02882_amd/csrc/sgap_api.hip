@@ -95,6 +95,7 @@ thread_local char t_last_error[256] = "";
 int g_tile_cols = 0;
 int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
 int g_rows_per_slot = 0;
+int g_persistent = 0;  // row-split: one workgroup per item keeps the rows in flight on a die close together
 
 bool g_profile = false;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
@@ -199,7 +200,7 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
         mark(ev0);
         // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
         // own consecutive rows by definition
-        err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, s);
+        err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, g_persistent != 0, s);
     } else {
         const bool par = strategy == SGAP_REDUCE_PARALLEL;
         const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);
@@ -271,6 +272,9 @@ int sgap_set_tuning(int knob, int value)
         case SGAP_TUNE_XCD_REMAP:
             if (value < -1 || value > 1) return fail(SGAP_ERR_INVALID_ARG, "xcd_remap must be -1, 0 or 1");
             g_xcd_remap = value;
+            return SGAP_OK;
+        case SGAP_TUNE_PERSISTENT:
+            g_persistent = value != 0;
             return SGAP_OK;
         case SGAP_TUNE_ROWS_PER_GROUP:
             if (value < 0 || value > 65536) return fail(SGAP_ERR_INVALID_ARG, "rows per group out of range");

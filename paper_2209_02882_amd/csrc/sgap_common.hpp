@@ -150,9 +150,11 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
 // g = lanes per row (1 for the serial strategy), rows_per_slot = rows a group
 // works through per work item (consecutive rows, or every slots-th row of the
 // block when `interleave` is set), tile_cols = columns per work item, xcds = 8
-// or 1, compute_units = CUs of the device (sizes the persistent grid).
+// or 1, compute_units = CUs of the device; persistent = launch only as many
+// workgroups as fit the chip and let each walk several items (else one
+// workgroup per item).
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                            int tile_cols, int xcds, int compute_units, hipStream_t s);
+                            int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
 // How an nnz-balanced kernel cuts the stored entries: tile = positions per LDS
 // tile, merge = tile mode of the merge rule, merge_log2 = log2 of the merge
 // block the zeroing pass must assume (tile in tile mode, group otherwise).

@@ -128,7 +128,7 @@ namespace {
 struct LaunchRowSplit {
     const SpmmArgs& a;
     int rows_per_slot, interleave, tile_cols, xcds, compute_units;
-    bool off32;
+    bool off32, persistent;
     hipStream_t s;
 
     // workgroups of this instance that one compute unit can hold at once
@@ -146,7 +146,7 @@ struct LaunchRowSplit {
         // a persistent grid must be resident all at once
         static const int per_cu_32 = resident_per_cu(row_split_kernel<G, LC, VEC, true>);
         static const int per_cu_64 = resident_per_cu(row_split_kernel<G, LC, VEC, false>);
-        const int max_grid = compute_units * (off32 ? per_cu_32 : per_cu_64);
+        const int max_grid = persistent ? compute_units * (off32 ? per_cu_32 : per_cu_64) : 0x7fffffff;
         constexpr int slots = kBlock / (G * LC);
         const int64_t rows_per_block = (int64_t)slots * rows_per_slot;
         TileSched ts;
@@ -157,6 +157,7 @@ struct LaunchRowSplit {
         ts.xcds = xcds;
         ts.items_per_xcd = (ts.items + xcds - 1) / xcds;
         int64_t wgs_per_xcd = max_grid / xcds > 0 ? max_grid / xcds : 1;
+        if (wgs_per_xcd * xcds > 0x7ffffff0LL) wgs_per_xcd = 0x7ffffff0LL / xcds;
         if (wgs_per_xcd > ts.items_per_xcd) wgs_per_xcd = ts.items_per_xcd;
         const unsigned grid = (unsigned)(wgs_per_xcd * xcds);
         if (off32)
@@ -171,9 +172,10 @@ struct LaunchRowSplit {
 }  // namespace
 
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                            int tile_cols, int xcds, int compute_units, hipStream_t s)
+                            int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s)
 {
-    LaunchRowSplit f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units, offsets_fit_32(a), s};
+    LaunchRowSplit f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units, offsets_fit_32(a),
+                     persistent, s};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }
