@@ -191,9 +191,9 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
         int rows_per_slot = par ? g_rows_per_slot : group_size;
         if (rows_per_slot <= 0) {
             // rows a group works through per item: enough stored entries per
-            // workgroup to amortise staging (about one LDS chunk)
+            // workgroup to amortise staging, few enough that neighbouring rows stay in flight together
             const int slots = 256 / (g * lc);
-            rows_per_slot = (int)(1536.0 / (avg_row * slots) + 0.5);
+            rows_per_slot = (int)(432.0 / (avg_row * slots) + 0.5);
             if (rows_per_slot < 1) rows_per_slot = 1;
             if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
         }

@@ -264,3 +264,55 @@ def test_copy_kernel():
     binding.sgap_copy_f32(x, y)
     torch.cuda.synchronize()
     assert torch.equal(x, y)
+
+
+def test_tuning_knobs_change_speed_not_results():
+    p = wl.make_problem("stencil27", scale_down=64, N=128)
+    rng = np.random.default_rng(3)
+    p.vals = wl.fill_values(rng, p.nnz, True)
+    p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    knobs = [(binding.SGAP_TUNE_TILE_COLS, v) for v in (0, 4, 30, 32, 64, 128, 1000)]
+    knobs += [(binding.SGAP_TUNE_XCD_REMAP, v) for v in (0, 1, -1)]
+    knobs += [(binding.SGAP_TUNE_ROWS_PER_GROUP, v) for v in (1, 3, 16, 0)]
+    knobs += [(binding.SGAP_TUNE_PERSISTENT, v) for v in (1, 0)]
+    try:
+        for knob, value in knobs:
+            binding.sgap_set_tuning(knob, value)
+            for point in POINTS:
+                if point[2] != "row_split":
+                    continue
+                assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"knob {knob}={value} {ids(point)}")
+    finally:
+        binding.sgap_set_tuning(binding.SGAP_TUNE_TILE_COLS, 0)
+        binding.sgap_set_tuning(binding.SGAP_TUNE_XCD_REMAP, -1)
+        binding.sgap_set_tuning(binding.SGAP_TUNE_ROWS_PER_GROUP, 0)
+        binding.sgap_set_tuning(binding.SGAP_TUNE_PERSISTENT, 0)
+    with pytest.raises(binding.SgapError):
+        binding.sgap_set_tuning(99, 1)
+
+
+def test_wide_matrix_offsets_need_64_bits():
+    # K*N*4 >= 2^32: the 32-bit offset fast path must not be taken
+    K, N, M = 1 << 22, 256, 300
+    rng = np.random.default_rng(21)
+    lengths = rng.integers(0, 12, size=M)
+    rowptr, colidx = wl.csr_from_lengths(rng, lengths, K)
+    # make sure the far end of B is touched
+    colidx[-1] = K - 1
+    vals = wl.fill_values(rng, colidx.size, True)
+    B = torch.zeros((K, N), dtype=torch.float32, device="cuda:0")
+    rows_used = np.unique(colidx)
+    Bsmall = wl.fill_values(rng, rows_used.size * N, True).reshape(-1, N)
+    B[torch.from_numpy(rows_used.astype(np.int64)).cuda()] = torch.from_numpy(Bsmall).cuda()
+    # oracle on a compacted copy (same rows of B, renumbered columns)
+    remap = np.searchsorted(rows_used, colidx).astype(np.int32)
+    C_ref, BND = oracle.spmm_csr(M, rows_used.size, N, rowptr, remap, vals, Bsmall)
+    rp, ci, va = (torch.from_numpy(x).cuda() for x in (rowptr, colidx, vals))
+    for point in POINTS:
+        C = torch.full((M, N), float("nan"), device="cuda:0")
+        binding.sgap_spmm_csr_ex(M, K, N, rp, ci, va, B, C, point[0], binding.STRATEGIES[point[1]],
+                                 binding.SCHEDULES[point[2]])
+        torch.cuda.synchronize()
+        assert_close(C, C_ref, BND, exact=True, what=f"64-bit offsets {ids(point)}")
