@@ -26,7 +26,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by the same counters on the library's plain copy kernel; keyed by
 # (workload, group, strategy, schedule).  See profiles/ for the runs.
-MEASURED_TRAFFIC_BYTES: dict = {}
+MEASURED_TRAFFIC_BYTES: dict = {
+    ("stencil27", 1, "parallel", "row_split"): 2_272_718_950,   # profiles/row_split_kernel_stencil27.md
+    ("stencil27", 1, "serial", "row_split"): 2_260_543_553,     # profiles/row_split_kernel_stencil27_serial.md
+    ("rmat", 32, "serial", "nnz_balanced"): 4_488_105_763,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
+    ("skewed", 64, "serial", "nnz_balanced"): 59_931_994_186,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
+}
 
 
 def log(*a):
