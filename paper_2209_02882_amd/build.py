@@ -8,7 +8,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsgap.so")
-SOURCES = ["sgap_api.hip", "sgap_row_split.hip", "sgap_nnz_parallel.hip", "sgap_nnz_serial.hip"]
+SOURCES = [
+    "sgap_api.hip", "sgap_row_split.hip",
+    "sgap_nnz_parallel.hip", "sgap_nnz_parallel_g1.hip", "sgap_nnz_parallel_g2.hip",
+    "sgap_nnz_parallel_g4_16.hip", "sgap_nnz_parallel_g8_32_64.hip",
+    "sgap_nnz_serial.hip", "sgap_nnz_serial_lc1_2.hip", "sgap_nnz_serial_lc4_8.hip",
+    "sgap_nnz_serial_lc16_32.hip", "sgap_nnz_serial_lc64.hip",
+]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU ops
@@ -26,7 +32,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int = 4) -> str:
+def build_library(jobs: int = 8) -> str:
     """Compile every source and link the shared library; always rebuilds."""
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))

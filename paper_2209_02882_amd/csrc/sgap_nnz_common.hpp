@@ -18,7 +18,10 @@
 
 namespace sgap {
 
-constexpr int kWindowCap = 1024;  // rowptr window entries cached in LDS
+constexpr int kWindowCap = 1024;              // rowptr window entries cached in LDS
+constexpr int kMergeLdsBudget = 34 * 1024;    // bytes of LDS accumulators tile mode may take
+constexpr int kParTile = 1024;                // positions per tile of the parallel strategy
+constexpr int kTileRowBatch = 256;            // tiles whose first rows a workgroup looks up at once
 
 // Largest r in [lo, hi] with rowptr[r] <= pos  (rowptr[lo] <= pos is given).
 __device__ __forceinline__ int32_t last_row_at_or_before(const int32_t* __restrict__ rowptr, int32_t lo,
@@ -82,33 +85,6 @@ __device__ __forceinline__ RowWindow load_row_window(const SpmmArgs& a, int32_t&
     w.n_first = first_above(s_win, kWindowCap + 1, first_pos) - 1;
     w.n_last = first_above(s_win, kWindowCap + 1, first_pos + w.cnt - 1) - 1;
     return w;
-}
-
-// Tiles are dealt to the persistent workgroups round-robin (workgroup b takes
-// tiles b, b + grid, ...), so that every workgroup gets its share of cheap and
-// of expensive stretches of A (long rows vs. many short or empty rows).  The
-// row of a tile's first position is found by the whole workgroup together:
-// each round probes rowptr at up to kBlock evenly spaced rows and keeps the
-// stretch between the last probe at or before `pos` and the next one.
-// Returns the largest r in [lo, hi] with rowptr[r] <= pos (rowptr[lo] <= pos
-// is given).  Block-uniform; contains barriers.
-__device__ __forceinline__ int32_t find_row_cooperative(const int32_t* __restrict__ rowptr, int32_t lo, int32_t hi,
-                                                        int32_t pos)
-{
-    const int tid = threadIdx.x;
-    while (lo < hi) {
-        const int64_t span = (int64_t)hi - lo;
-        const int64_t step = (span + kBlock - 1) / kBlock;  // >= 1
-        int64_t r = (int64_t)lo + (tid + 1) * step;
-        if (r > hi) r = hi;
-        const int cnt = __syncthreads_count(rowptr[r] <= pos);  // probes are sorted: the first cnt hold
-        if (cnt == kBlock) return hi;  // the last probe is hi itself
-        int64_t next = (int64_t)lo + (cnt + 1) * step;  // first probe beyond pos
-        if (next > hi) next = hi;
-        if (cnt > 0) lo = (int32_t)((int64_t)lo + cnt * step);
-        hi = (int32_t)next - 1;
-    }
-    return lo;
 }
 
 template <int VEC>

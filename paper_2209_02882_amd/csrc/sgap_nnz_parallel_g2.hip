@@ -1,0 +1,16 @@
+// Instances of the nnz-balanced parallel kernel for group sizes 2.
+#include "sgap_nnz_parallel_impl.hpp"
+
+namespace sgap {
+
+hipError_t launch_nnz_parallel_g2(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, bool merge,
+                                  hipStream_t s)
+{
+    using nnz_parallel_detail::launch_group;
+    switch (a.group) {
+        case 2: return launch_group<2>(a, lc, vec, compute_units, nnz_hint, merge, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sgap

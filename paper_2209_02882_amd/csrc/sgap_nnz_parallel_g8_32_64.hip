@@ -1,0 +1,18 @@
+// Instances of the nnz-balanced parallel kernel for group sizes 8, 32, 64.
+#include "sgap_nnz_parallel_impl.hpp"
+
+namespace sgap {
+
+hipError_t launch_nnz_parallel_g8_32_64(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, bool merge,
+                                        hipStream_t s)
+{
+    using nnz_parallel_detail::launch_group;
+    switch (a.group) {
+        case 8: return launch_group<8>(a, lc, vec, compute_units, nnz_hint, merge, s);
+        case 32: return launch_group<32>(a, lc, vec, compute_units, nnz_hint, merge, s);
+        case 64: return launch_group<64>(a, lc, vec, compute_units, nnz_hint, merge, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sgap
