@@ -93,6 +93,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="stencil27")
+    ap.add_argument("--ncols", type=int, default=None, help="override N, the number of dense columns")
     ap.add_argument("--sweep-iters", type=int, default=3)
     ap.add_argument("--point", default=None, help="fix the point: e.g. 8,parallel,row_split (skips the sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -112,7 +113,7 @@ def main():
     binding.load()
 
     t0 = time.perf_counter()
-    p = wl.make_problem(a.workload)
+    p = wl.make_problem(a.workload, N=a.ncols)
     log(f"[bench] workload {a.workload}: {p.row_stats()} generated in {time.perf_counter() - t0:.1f}s")
 
     from paper_2209_02882_amd.device import POINTS, DeviceProblem
