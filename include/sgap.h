@@ -149,8 +149,22 @@ int sgap_version(void);
  *                        work item in the row-split parallel strategy (the
  *                        serial strategy takes group_size rows by definition);
  *                        0 = automatic, from the mean row length.
+ *   SGAP_TUNE_PERSISTENT 1: the row-split schedule launches only as many
+ *                        workgroups as the chip holds at once and each loops
+ *                        over work items; 0 (default): one workgroup per item.
+ *   SGAP_TUNE_NNZ_TILE   stored entries per tile of the nnz-balanced serial
+ *                        strategy: 256, 512, 1024 or 2048 (the two small ones
+ *                        need N % 4 == 0 and 16-byte aligned B and C, else
+ *                        the automatic choice is kept); 0 = automatic, from
+ *                        nnz and the size of the chip.
  */
-typedef enum { SGAP_TUNE_TILE_COLS = 0, SGAP_TUNE_XCD_REMAP = 1, SGAP_TUNE_ROWS_PER_GROUP = 2, SGAP_TUNE_PERSISTENT = 3 } sgap_tuning_knob;
+typedef enum {
+    SGAP_TUNE_TILE_COLS = 0,
+    SGAP_TUNE_XCD_REMAP = 1,
+    SGAP_TUNE_ROWS_PER_GROUP = 2,
+    SGAP_TUNE_PERSISTENT = 3,
+    SGAP_TUNE_NNZ_TILE = 4
+} sgap_tuning_knob;
 int sgap_set_tuning(int knob, int value);
 
 /*

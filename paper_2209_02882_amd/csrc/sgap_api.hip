@@ -95,6 +95,7 @@ thread_local char t_last_error[256] = "";
 int g_tile_cols = 0;
 int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
 int g_rows_per_slot = 0;
+int g_nnz_tile = 0;    // nnz-balanced serial: forced tile size, 0 = automatic
 int g_persistent = 0;  // row-split: one workgroup per item keeps the rows in flight on a die close together
 
 bool g_profile = false;
@@ -204,12 +205,13 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     } else {
         const bool par = strategy == SGAP_REDUCE_PARALLEL;
         const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);
-        const NnzPlan plan = par ? plan_nnz_parallel(group_size, lc, vec) : plan_nnz_serial(group_size, lc, vec);
+        const NnzPlan plan = par ? plan_nnz_parallel(group_size, lc, vec)
+                                 : plan_nnz_serial(group_size, lc, vec, nnz_hint, compute_units(), g_nnz_tile);
         err = launch_nnz_zero_rows(a, vec, plan.merge_log2, s);
         if (err == hipSuccess) {
             mark(ev0);
             err = par ? launch_nnz_parallel(a, lc, vec, compute_units(), nnz_hint, s)
-                      : launch_nnz_serial(a, lc, vec, compute_units(), nnz_hint, s);
+                      : launch_nnz_serial(a, lc, vec, plan, compute_units(), nnz_hint, s);
         }
     }
     if (ev0) {
@@ -275,6 +277,11 @@ int sgap_set_tuning(int knob, int value)
             return SGAP_OK;
         case SGAP_TUNE_PERSISTENT:
             g_persistent = value != 0;
+            return SGAP_OK;
+        case SGAP_TUNE_NNZ_TILE:
+            if (value != 0 && value != 256 && value != 512 && value != 1024 && value != 2048)
+                return fail(SGAP_ERR_INVALID_ARG, "nnz tile must be 0, 256, 512, 1024 or 2048");
+            g_nnz_tile = value;
             return SGAP_OK;
         case SGAP_TUNE_ROWS_PER_GROUP:
             if (value < 0 || value > 65536) return fail(SGAP_ERR_INVALID_ARG, "rows per group out of range");

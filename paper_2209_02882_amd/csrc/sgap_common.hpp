@@ -145,6 +145,16 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
     for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(p + i, r.v[i]);
 }
 
+// How an nnz-balanced kernel cuts the stored entries: tile = positions per LDS
+// tile, merge = tile mode of the merge rule, merge_log2 = log2 of the merge
+// block the zeroing pass must assume (tile in tile mode, group otherwise).
+struct NnzPlan {
+    int tile;
+    bool merge;
+    int merge_log2;
+};
+NnzPlan plan_nnz_serial(int group, int lc, int vec, int64_t nnz_hint, int compute_units, int forced_tile);
+NnzPlan plan_nnz_parallel(int group, int lc, int vec);
 // ---- host-side launchers, one per kernel family (defined in the .hip files)
 // lc = chunk lanes per row (power of two), vec = columns per lane (1, 2, 4).
 // g = lanes per row (1 for the serial strategy), rows_per_slot = rows a group
@@ -155,20 +165,11 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
 // workgroup per item).
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
                             int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
-// How an nnz-balanced kernel cuts the stored entries: tile = positions per LDS
-// tile, merge = tile mode of the merge rule, merge_log2 = log2 of the merge
-// block the zeroing pass must assume (tile in tile mode, group otherwise).
-struct NnzPlan {
-    int tile;
-    bool merge;
-    int merge_log2;
-};
-NnzPlan plan_nnz_serial(int group, int lc, int vec);
-NnzPlan plan_nnz_parallel(int group, int lc, int vec);
 hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, int merge_log2, hipStream_t s);
 // compute_units sizes the persistent grid; nnz_hint (-1 = unknown) caps it.
 hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
-hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
+hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, const NnzPlan& plan, int compute_units,
+                             int64_t nnz_hint, hipStream_t s);
 hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);

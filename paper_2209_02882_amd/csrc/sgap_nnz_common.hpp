@@ -87,6 +87,58 @@ __device__ __forceinline__ RowWindow load_row_window(const SpmmArgs& a, int32_t&
     return w;
 }
 
+// The whole workgroup looks for one row together: each round probes rowptr at
+// up to kBlock evenly spaced rows and keeps the stretch between the last
+// probe at or before `pos` and the next one (3 rounds for 2 M rows, where a
+// single thread's bisection takes 21 dependent loads).  Returns the largest r
+// in [lo, hi] with rowptr[r] <= pos (rowptr[lo] <= pos is given).
+// Block-uniform; contains barriers.
+__device__ __forceinline__ int32_t find_row_cooperative(const int32_t* __restrict__ rowptr, int32_t lo, int32_t hi,
+                                                        int32_t pos)
+{
+    const int tid = threadIdx.x;
+    while (lo < hi) {
+        const int64_t span = (int64_t)hi - lo;
+        const int64_t step = (span + kBlock - 1) / kBlock;  // >= 1
+        int64_t r = (int64_t)lo + (tid + 1) * step;
+        if (r > hi) r = hi;
+        const int cnt = __syncthreads_count(rowptr[r] <= pos);  // probes are sorted: the first cnt hold
+        if (cnt == kBlock) return hi;  // the last probe is hi itself
+        int64_t next = (int64_t)lo + (cnt + 1) * step;  // first probe beyond pos
+        if (next > hi) next = hi;
+        if (cnt > 0) lo = (int32_t)((int64_t)lo + cnt * step);
+        hi = (int32_t)next - 1;
+    }
+    return lo;
+}
+
+// Rows of the first positions of this workgroup's tiles number j0 .. j0+n-1
+// (tile j is global tile blockIdx.x + j*gridDim.x of `tile` positions each),
+// left in s_tile_row[0..n).  A workgroup with many tiles lets each thread
+// bisect for one tile; one with a few searches for them together, which is
+// what bounds the run time of small matrices.  Block-uniform; s_tile_row is
+// ready on return.
+constexpr int kFewTiles = 4;
+__device__ __forceinline__ void find_tile_rows(const SpmmArgs& a, int64_t j0, int64_t my_tiles, int tile,
+                                               int32_t* __restrict__ s_tile_row)
+{
+    const int32_t M = (int32_t)a.M;
+    const int tid = threadIdx.x;
+    const int64_t n = my_tiles - j0 < kTileRowBatch ? my_tiles - j0 : kTileRowBatch;
+    __syncthreads();  // the previous batch's rows are no longer needed
+    if (n <= kFewTiles) {
+        int32_t lo = 0;
+        for (int j = 0; j < (int)n; ++j) {
+            lo = find_row_cooperative(a.rowptr, lo, M - 1, (int32_t)((blockIdx.x + (j0 + j) * gridDim.x) * tile));
+            if (tid == 0) s_tile_row[j] = lo;
+        }
+    } else if (tid < n) {
+        s_tile_row[tid] =
+            last_row_at_or_before(a.rowptr, 0, M - 1, (int32_t)((blockIdx.x + (j0 + tid) * gridDim.x) * tile));
+    }
+    __syncthreads();
+}
+
 template <int VEC>
 __device__ __forceinline__ void write_out(const SpmmArgs& a, int32_t row, int64_t k, bool plain,
                                           const Vec<VEC>& x)

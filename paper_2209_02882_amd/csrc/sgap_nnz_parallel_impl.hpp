@@ -199,12 +199,7 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
     };
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        // rows of the first positions of the next batch of tiles, one bisection per thread
-        __syncthreads();
-        if (j0 + tid < my_tiles)
-            s_tile_row[tid] = last_row_at_or_before(a.rowptr, 0, M - 1,
-                                                    (int32_t)((blockIdx.x + (j0 + tid) * gridDim.x) * kParTile));
-        __syncthreads();
+        find_tile_rows(a, j0, my_tiles, kParTile, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
         fetch_tile(blockIdx.x + j0 * gridDim.x, s_tile_row[0]);
 

@@ -7,12 +7,36 @@
 namespace sgap {
 
 // Tile size and merge mode of the serial kernel for a given layout; the
-// zeroing pass must be launched with the same merge_log2.
-NnzPlan plan_nnz_serial(int group, int lc, int vec)
+// zeroing pass must be launched with the same merge_log2.  forced_tile > 0
+// overrides the choice of the tile size.
+NnzPlan plan_nnz_serial(int group, int lc, int vec, int64_t nnz_hint, int compute_units, int forced_tile)
 {
     NnzPlan p;
     // keep every entry lane busy: tile >= lanes * group; 1024 or 2048 positions
     p.tile = (kBlock / lc) * group > 1024 ? 2048 : 1024;
+    // A small matrix gives the chip only a few tiles per workgroup, or fewer
+    // tiles than the chip holds workgroups (about 4 per compute unit).  Rate a
+    // tile size by the share of the chip that is busy over the rounds of
+    // tiles, the last of which is only partly filled, and take the largest
+    // tile (down to 256 positions) that keeps 85 % busy, else the best one.
+    if (forced_tile >= 1024 || (forced_tile > 0 && vec == 4)) {
+        p.tile = forced_tile;
+    } else if (nnz_hint > 0 && vec == 4) {
+        const double resident = 4.0 * compute_units;
+        int best_tile = p.tile;
+        double best_busy = 0.0;
+        for (int tile = p.tile; tile >= 256; tile /= 2) {
+            const double rounds = (double)((nnz_hint + tile - 1) / tile) / resident;
+            const double whole = (double)(int64_t)(rounds + 0.999999);
+            const double busy = rounds / whole;
+            if (busy > best_busy + 1e-9) {
+                best_busy = busy;
+                best_tile = tile;
+            }
+            if (busy >= 0.85) break;
+        }
+        p.tile = best_tile;
+    }
     const int nslots = p.tile / group + 1;
     p.merge = nslots * (lc * vec * 4 + 8) <= kMergeLdsBudget;
     int lg = 0;
@@ -27,9 +51,9 @@ hipError_t launch_nnz_serial_lc4_8(const SpmmArgs&, int, int, int, int64_t, int,
 hipError_t launch_nnz_serial_lc16_32(const SpmmArgs&, int, int, int, int64_t, int, bool, hipStream_t);
 hipError_t launch_nnz_serial_lc64(const SpmmArgs&, int, int, int, int64_t, int, bool, hipStream_t);
 
-hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s)
+hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, const NnzPlan& plan, int compute_units,
+                             int64_t nnz_hint, hipStream_t s)
 {
-    const NnzPlan plan = plan_nnz_serial(a.group, lc, vec);
     switch (lc) {
         case 1: case 2: return launch_nnz_serial_lc1_2(a, lc, vec, compute_units, nnz_hint, plan.tile, plan.merge, s);
         case 4: case 8: return launch_nnz_serial_lc4_8(a, lc, vec, compute_units, nnz_hint, plan.tile, plan.merge, s);

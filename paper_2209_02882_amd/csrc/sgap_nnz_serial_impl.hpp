@@ -185,12 +185,7 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
     };
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        // rows of the first positions of the next batch of tiles, one bisection per thread
-        __syncthreads();
-        if (j0 + tid < my_tiles)
-            s_tile_row[tid] = last_row_at_or_before(a.rowptr, 0, M - 1,
-                                                    (int32_t)((blockIdx.x + (j0 + tid) * gridDim.x) * TILE));
-        __syncthreads();
+        find_tile_rows(a, j0, my_tiles, TILE, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
         fetch_tile(blockIdx.x + j0 * gridDim.x, s_tile_row[0]);
 
@@ -254,7 +249,7 @@ struct Launch {
     {
         const int nslots = tile / a.group + 1;
         const int smem = tile * (int)sizeof(StagedEntry) + (MERGE ? nslots * (LC * VEC * 4 + 8) : 0);
-        static int cached[7];  // [log2 group] resident workgroups per CU, 0 = not asked yet
+        static int cached[7];  // [log2 group] resident workgroups per CU of this instance, 0 = not asked yet
         int& per_cu = cached[a.log2_group];
         if (per_cu == 0) per_cu = resident_per_cu(nnz_serial_kernel<LC, VEC, OFF32, MERGE, EPT>, smem);
         const int grid = persistent_grid(per_cu, compute_units, nnz_hint, tile);
@@ -264,6 +259,11 @@ struct Launch {
     template <int LC, int VEC, bool OFF32, bool MERGE>
     void pick_tile() const
     {
+        // the small tiles exist for 16-byte lanes only (plan_nnz_serial)
+        if constexpr (VEC == 4) {
+            if (tile == 256) return go<LC, VEC, OFF32, MERGE, 1>();
+            if (tile == 512) return go<LC, VEC, OFF32, MERGE, 2>();
+        }
         if (tile == 1024) go<LC, VEC, OFF32, MERGE, 4>();
         else go<LC, VEC, OFF32, MERGE, 8>();
     }

@@ -293,6 +293,30 @@ def test_tuning_knobs_change_speed_not_results():
         binding.sgap_set_tuning(99, 1)
 
 
+@pytest.mark.parametrize("name", ["powerlaw", "rmat", "skewed"])
+def test_nnz_tile_sizes(name):
+    # every tile size of the nnz-balanced serial kernel, on inputs with rows
+    # far longer than a tile, rows without entries and many tiles per workgroup
+    p = wl.make_problem(name, **{"powerlaw": dict(scale_down=2), "rmat": dict(scale_down=64),
+                                 "skewed": dict(scale_down=25, N=64)}[name])
+    rng = np.random.default_rng(5)
+    p.vals = wl.fill_values(rng, p.nnz, True)
+    p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    try:
+        for tile in (256, 512, 1024, 2048, 0):
+            binding.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, tile)
+            for point in POINTS:
+                if point[1:] != ("serial", "nnz_balanced"):
+                    continue
+                assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"tile {tile} {ids(point)}")
+    finally:
+        binding.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, 0)
+    with pytest.raises(binding.SgapError):
+        binding.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, 300)
+
+
 def test_wide_matrix_offsets_need_64_bits():
     # K*N*4 >= 2^32: the 32-bit offset fast path must not be taken
     K, N, M = 1 << 22, 256, 300
