@@ -126,6 +126,24 @@ int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N,
                      int group_size, int strategy, int schedule,
                      int64_t nnz_hint, void* stream);
 
+/*
+ * Row-split SpMM with the tiling and the synchronisation granularity set
+ * apart: the point {<1/g row, c col>, r} of the paper's design space
+ * (Section 4; Table 1 sweeps r below g).  `group_size` = g lanes share a row
+ * and split its stored entries; every `reduce_size` = r neighbouring lanes of
+ * them (power of two, 1 <= r <= g) tree-sum their partial sums, and the g/r
+ * sub-group sums of a row are merged into C with atomic adds (r = 1: every
+ * lane adds its own sum, the "Atomics" strategy of Section 5.1).  r = g is
+ * sgap_spmm_csr_ex with the parallel strategy and the row-split schedule:
+ * plain stores, no atomics.  For r < g the library zeroes C first, and the
+ * order of the atomic adds, hence the fp32 rounding, varies between runs.
+ * Other arguments, ownership and errors as for sgap_spmm_csr_ex.
+ */
+int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N,
+                     const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                     const float* B, float* C,
+                     int group_size, int reduce_size, int64_t nnz_hint, void* stream);
+
 /* Text for a status code / detail of this thread's last failure (static or
  * thread-local storage; never free). */
 const char* sgap_status_string(int status);
@@ -189,9 +207,14 @@ int sgap_profile_collect(double* total_ms, int* count);
  *   sgap_debug_group_seg_reduce: in fp32[64], span int32[64] device (span[l] =
  *     how many following members of lane l's group continue lane l's run,
  *     0..group_size-1) -> out[l] = in[l] + the next span[l] members' inputs.
+ *   sgap_debug_group_partial_reduce: the same for sub-groups of reduce_size
+ *     members (power of two <= group_size): the first lane of every sub-group
+ *     receives the sub-group's sum, other lanes 0.
  */
 int sgap_debug_group_reduce(const float* in, float* out, int group_size,
                             int lanes_per_row, void* stream);
+int sgap_debug_group_partial_reduce(const float* in, float* out, int group_size,
+                                    int reduce_size, int lanes_per_row, void* stream);
 int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out,
                                 int group_size, int lanes_per_row, void* stream);
 

@@ -34,6 +34,7 @@ EXPORTS = {
     "sgap_get_schedule": (_int, []),
     "sgap_spmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_spmm_csr_ex": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
+    "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
@@ -41,6 +42,7 @@ EXPORTS = {
     "sgap_profile_enable": (_int, [_int]),
     "sgap_profile_collect": (_int, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_int)]),
     "sgap_debug_group_reduce": (_int, [_p, _p, _int, _int, _p]),
+    "sgap_debug_group_partial_reduce": (_int, [_p, _p, _int, _int, _int, _p]),
     "sgap_debug_group_seg_reduce": (_int, [_p, _p, _p, _int, _int, _p]),
     "sgap_copy_f32": (_int, [_p, _p, _i64, _p]),
 }
@@ -164,6 +166,25 @@ def sgap_profile_collect():
     count = ctypes.c_int(0)
     _check(load().sgap_profile_collect(ctypes.byref(total), ctypes.byref(count)))
     return total.value, count.value
+
+
+def sgap_spmm_csr_gr(M, K, N, rowptr, colidx, vals, B, C, group_size, reduce_size, nnz_hint=None,
+                     stream=None) -> None:
+    """Row-split C = A_csr * B with group_size lanes per row reducing in
+    sub-groups of reduce_size lanes (see include/sgap.h)."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    _check(load().sgap_spmm_csr_gr(M, K, N, *ptrs, int(group_size), int(reduce_size), int(nnz_hint),
+                                   _stream_ptr(stream)))
+
+
+def sgap_debug_group_partial_reduce(inp, out, group_size, reduce_size, lanes_per_row, stream=None) -> None:
+    import torch
+
+    _check(load().sgap_debug_group_partial_reduce(
+        _dev_ptr(inp, torch.float32, "in"), _dev_ptr(out, torch.float32, "out"),
+        int(group_size), int(reduce_size), int(lanes_per_row), _stream_ptr(stream)))
 
 
 def sgap_debug_group_reduce(inp, out, group_size, lanes_per_row, stream=None) -> None:

@@ -15,12 +15,12 @@ namespace sgap {
 // ---- small kernels that belong to the boundary, not to a schedule ---------
 
 template <int G, int LC>
-__global__ void debug_group_reduce_kernel(const float* __restrict__ in, float* __restrict__ out)
+__global__ void debug_group_reduce_kernel(const float* __restrict__ in, float* __restrict__ out, int r)
 {
     const int lane = threadIdx.x;
-    const float s = group_tree_sum<G, LC>(in[lane]);
+    const float s = r == G ? group_tree_sum<G, LC>(in[lane]) : group_partial_sum<G, LC>(in[lane], r * LC);
     const int member = (lane / LC) % G;
-    out[lane] = member == 0 ? s : 0.0f;
+    out[lane] = member % r == 0 ? s : 0.0f;
 }
 
 template <int G, int LC>
@@ -45,11 +45,12 @@ namespace {
 struct LaunchDebugReduce {
     const float* in;
     float* out;
+    int r;
     hipStream_t s;
     template <int G, int LC, int VEC>
     void operator()() const
     {
-        hipLaunchKernelGGL((debug_group_reduce_kernel<G, LC>), dim3(1), dim3(kWave), 0, s, in, out);
+        hipLaunchKernelGGL((debug_group_reduce_kernel<G, LC>), dim3(1), dim3(kWave), 0, s, in, out, r);
     }
 };
 struct LaunchDebugSegReduce {
@@ -65,9 +66,9 @@ struct LaunchDebugSegReduce {
 };
 }  // namespace
 
-hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s)
+hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, int lc, hipStream_t s)
 {
-    if (!dispatch_group(g, lc, 1, LaunchDebugReduce{in, out, s})) return hipErrorInvalidValue;
+    if (!dispatch_group(g, lc, 1, LaunchDebugReduce{in, out, r, s})) return hipErrorInvalidValue;
     return hipGetLastError();
 }
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
@@ -140,8 +141,11 @@ int compute_units()
 }
 
 int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
-              const float* B, float* C, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream)
+              const float* B, float* C, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream,
+              int reduce_size = 0)
 {
+    // reduce_size = 0: the group reduces as a whole; 1 <= reduce_size < group_size
+    // (row-split, parallel strategy only): sub-groups merged with atomics
     using namespace sgap;
     if (M < 0 || K < 0 || N < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
     if (M > 2147483646LL || N > 2147483647LL || K > 2147483647LL)
@@ -152,6 +156,9 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
         return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
     if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
+    if (reduce_size != 0 && (!is_pow2_group(reduce_size) || reduce_size > group_size))
+        return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
+    if (reduce_size == group_size) reduce_size = 0;
     if (M == 0 || N == 0) return SGAP_OK;
     if (!rowptr || !C) return fail(SGAP_ERR_INVALID_ARG, "rowptr and C must not be null");
     if (K > 0 && !B) return fail(SGAP_ERR_INVALID_ARG, "B must not be null when K > 0");
@@ -198,10 +205,21 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
             if (rows_per_slot < 1) rows_per_slot = 1;
             if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
         }
-        mark(ev0);
-        // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
-        // own consecutive rows by definition
-        err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, g_persistent != 0, s);
+        if (reduce_size != 0) {
+            // every row receives atomic adds
+            err = launch_nnz_zero_rows(a, vec, -1, s);
+            if (err == hipSuccess) {
+                mark(ev0);
+                err = launch_row_split_partial(a, g, reduce_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus,
+                                               g_persistent != 0, s);
+            }
+        } else {
+            mark(ev0);
+            // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
+            // own consecutive rows by definition
+            err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, g_persistent != 0,
+                                   s);
+        }
     } else {
         const bool par = strategy == SGAP_REDUCE_PARALLEL;
         const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);
@@ -247,6 +265,15 @@ int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, con
                      int64_t nnz_hint, void* stream)
 {
     return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, schedule, nnz_hint, stream);
+}
+
+int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                     const float* vals, const float* B, float* C, int group_size, int reduce_size, int64_t nnz_hint,
+                     void* stream)
+{
+    if (reduce_size < 1) return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, SGAP_REDUCE_PARALLEL, SGAP_SCHED_ROW_SPLIT,
+                     nnz_hint, stream, reduce_size);
 }
 
 const char* sgap_status_string(int status)
@@ -322,10 +349,16 @@ int sgap_profile_collect(double* total_ms, int* count)
 
 int sgap_debug_group_reduce(const float* in, float* out, int group_size, int lanes_per_row, void* stream)
 {
+    return sgap_debug_group_partial_reduce(in, out, group_size, group_size, lanes_per_row, stream);
+}
+
+int sgap_debug_group_partial_reduce(const float* in, float* out, int group_size, int reduce_size, int lanes_per_row,
+                                    void* stream)
+{
     if (!in || !out || !is_pow2_group(group_size) || !is_pow2_group(lanes_per_row) ||
-        group_size * lanes_per_row > 64)
+        group_size * lanes_per_row > 64 || !is_pow2_group(reduce_size) || reduce_size > group_size)
         return fail(SGAP_ERR_INVALID_ARG, "bad group layout");
-    hipError_t err = sgap::launch_debug_group_reduce(in, out, group_size, lanes_per_row,
+    hipError_t err = sgap::launch_debug_group_reduce(in, out, group_size, reduce_size, lanes_per_row,
                                                      reinterpret_cast<hipStream_t>(stream));
     if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
     return SGAP_OK;

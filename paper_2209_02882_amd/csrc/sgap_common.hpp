@@ -165,12 +165,19 @@ NnzPlan plan_nnz_parallel(int group, int lc, int vec);
 // workgroup per item).
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
                             int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
+// the same with g lanes per row reducing in sub-groups of r < g lanes whose sums
+// are merged with atomics; C must have been zeroed (launch_nnz_zero_rows, -1)
+hipError_t launch_row_split_partial(const SpmmArgs& a, int g, int r, int lc, int vec, int rows_per_slot,
+                                    int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
+// zero the rows of C that receive atomic adds under a merge block of
+// 2^merge_log2 positions, and the rows without entries; merge_log2 = -1: all rows
 hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, int merge_log2, hipStream_t s);
 // compute_units sizes the persistent grid; nnz_hint (-1 = unknown) caps it.
 hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s);
 hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, const NnzPlan& plan, int compute_units,
                              int64_t nnz_hint, hipStream_t s);
-hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int lc, hipStream_t s);
+// r = members per reducing sub-group (r = g: the whole group)
+hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, int lc, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s);

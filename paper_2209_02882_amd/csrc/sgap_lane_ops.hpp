@@ -87,6 +87,29 @@ __device__ __forceinline__ float group_tree_sum(float v)
     return tree_down<(G * LC) / 2, LC>(v);
 }
 
+template <int S, int LC>
+__device__ __forceinline__ float tree_down_below(float v, int limit)
+{
+    if constexpr (S >= LC && S >= 1) {
+        if (S < limit) v = tree_step<S>(v);  // wave-uniform condition
+        return tree_down_below<S / 2, LC>(v, limit);
+    } else {
+        return v;
+    }
+}
+
+// Sums over sub-groups: the G members of a group reduce in aligned sub-groups
+// of R = reduce_lanes / LC members (R a power of two, 1 <= R <= G; reduce_lanes
+// is the same in every lane).  The result is valid in the first member of each
+// sub-group.  This is the reduction of {<1/g row, c col>, r} with r < g
+// (Section 4): the tiling uses G lanes per row, the synchronisation R.
+template <int G, int LC>
+__device__ __forceinline__ float group_partial_sum(float v, int reduce_lanes)
+{
+    static_assert(G * LC <= 64, "a group lives inside one wavefront");
+    return tree_down_below<(G * LC) / 2, LC>(v, reduce_lanes);
+}
+
 // Value of the lane S above, for every lane whose source lies in the same
 // aligned block of SPAN lanes.
 template <int S, int SPAN>

@@ -8,7 +8,7 @@ namespace sgap {
 
 // Rows that will receive global atomic adds (their positions straddle an
 // aligned merge block of 2^merge_log2 positions) and rows without stored
-// entries are set to +0.
+// entries are set to +0; merge_log2 < 0: every row is.
 // thread = (row_lane, chunk); chunk lanes stride over the row's columns.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void zero_rows_kernel(SpmmArgs a, int lcz, int merge_log2)
@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kBlock) void zero_rows_kernel(SpmmArgs a, int lcz, 
     if (row >= a.M) return;
     const int32_t p_begin = a.rowptr[row];
     const int32_t p_end = a.rowptr[row + 1];
-    const bool plain = p_end > p_begin && (p_begin >> merge_log2) == ((p_end - 1) >> merge_log2);
+    const bool plain = merge_log2 >= 0 && p_end > p_begin && (p_begin >> merge_log2) == ((p_end - 1) >> merge_log2);
     if (plain) return;
     Vec<VEC> z;
     z.zero();

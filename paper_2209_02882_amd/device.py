@@ -10,6 +10,8 @@ from . import binding
 # every (group_size, strategy, schedule) point of the design space
 POINTS = [(g, st, sc) for sc in ("row_split", "nnz_balanced") for st in ("parallel", "serial")
           for g in binding.GROUP_SIZES]
+# the points {<1/g row, c col>, r} with the reduction narrower than the tiling
+GR_POINTS = [(g, r) for g in binding.GROUP_SIZES for r in binding.GROUP_SIZES if r < g]
 
 
 class DeviceProblem:
@@ -33,6 +35,19 @@ class DeviceProblem:
         binding.sgap_spmm_csr_ex(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, self.B, C,
                                  group, binding.STRATEGIES[strategy], binding.SCHEDULES[schedule],
                                  nnz_hint=nnz_hint, stream=stream)
+
+    def launch_gr(self, C, group, reduce_size, nnz_hint=None, stream=None):
+        """Enqueue the row-split point with `group` lanes per row reducing in
+        sub-groups of `reduce_size` lanes (asynchronous)."""
+        p = self.p
+        binding.sgap_spmm_csr_gr(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, self.B, C,
+                                 group, reduce_size, nnz_hint=nnz_hint, stream=stream)
+
+    def run_gr(self, group, reduce_size, poison=True):
+        C = self.new_output(poison)
+        self.launch_gr(C, group, reduce_size)
+        torch.cuda.synchronize()
+        return C
 
     def run(self, group, strategy, schedule, poison=True, C=None, nnz_hint=None):
         """Run one point to completion; by default C starts filled with NaN so

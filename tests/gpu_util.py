@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 import oracle
-from paper_2209_02882_amd.device import POINTS, DeviceProblem  # noqa: F401
+from paper_2209_02882_amd.device import GR_POINTS, POINTS, DeviceProblem  # noqa: F401
 
 TOL = 1e-5  # |C - C_ref| <= TOL * (|A| |B|) elementwise, fp32 atomics reorder sums
 

@@ -8,7 +8,7 @@ import oracle
 from paper_2209_02882_amd import binding
 from paper_2209_02882_amd import workloads as wl
 
-from gpu_util import POINTS, DeviceProblem, assert_close, full_reference, sample_rows
+from gpu_util import GR_POINTS, POINTS, DeviceProblem, assert_close, full_reference, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -34,6 +34,25 @@ def test_group_tree_sum_every_layout():
                 if member == 0:
                     want[lane] = sum(x[lane + m * lc] for m in range(g))
             assert np.array_equal(got, want), f"group {g}, lanes per row {lc}"
+            lc *= 2
+
+
+def test_group_partial_sum_every_layout_and_width():
+    rng = np.random.default_rng(11)
+    for g in binding.GROUP_SIZES:
+        lc = 1
+        while g * lc <= 64:
+            for r in [x for x in binding.GROUP_SIZES if x <= g]:
+                x = rng.integers(-8, 9, size=64).astype(np.float32)
+                out = torch.full((64,), float("nan"), device="cuda:0")
+                binding.sgap_debug_group_partial_reduce(torch.from_numpy(x).cuda(), out, g, r, lc)
+                got = out.cpu().numpy()
+                want = np.zeros(64, np.float32)
+                for lane in range(64):
+                    member = (lane // lc) % g
+                    if member % r == 0:
+                        want[lane] = sum(x[lane + m * lc] for m in range(r))
+                assert np.array_equal(got, want), f"group {g}, reduce {r}, lanes per row {lc}"
             lc *= 2
 
 
@@ -291,6 +310,36 @@ def test_tuning_knobs_change_speed_not_results():
         binding.sgap_set_tuning(binding.SGAP_TUNE_PERSISTENT, 0)
     with pytest.raises(binding.SgapError):
         binding.sgap_set_tuning(99, 1)
+
+
+@pytest.mark.parametrize("name,kw", [("uniform10", {}), ("powerlaw", dict(scale_down=8)),
+                                     ("stencil27", dict(scale_down=64)), ("skewed", dict(scale_down=25, N=64)),
+                                     ("uniform10", dict(N=6)), ("uniform10", dict(N=7)), ("powerlaw", dict(scale_down=8, N=4))])
+def test_reduce_width_below_group_size(name, kw):
+    # {<1/g row, c col>, r} for every r < g: sub-group sums merged with atomics
+    p = wl.make_problem(name, **kw)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for g, r in GR_POINTS:
+        assert_close(dp.run_gr(g, r), C_ref, BND, what=f"{name} {kw} g={g} r={r}")
+    # r = g is the plain-store point
+    assert torch.equal(dp.run_gr(16, 16), dp.run(16, "parallel", "row_split"))
+    rng = np.random.default_rng(17)
+    p.vals = wl.fill_values(rng, p.nnz, True)
+    p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for g, r in GR_POINTS:
+        assert_close(dp.run_gr(g, r), C_ref, BND, exact=True, what=f"{name} {kw} int g={g} r={r}")
+
+
+def test_reduce_width_argument_checks():
+    p = wl.make_problem("uniform10")
+    dp = DeviceProblem(p)
+    C = dp.new_output()
+    for g, r in [(8, 16), (8, 3), (8, 0), (8, -1), (3, 1), (128, 8)]:
+        with pytest.raises(binding.SgapError):
+            dp.launch_gr(C, g, r)
 
 
 @pytest.mark.parametrize("name", ["powerlaw", "rmat", "skewed"])
