@@ -144,6 +144,37 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N,
                      const float* B, float* C,
                      int group_size, int reduce_size, int64_t nnz_hint, void* stream);
 
+/*
+ * Tuner over the design space: the paper closes (Section 8) by proposing that
+ * the space be exposed as an auto-tuning interface, and Table 5 measures what
+ * a per-matrix choice gains over the best fixed point.  Times every
+ * (group_size, strategy, schedule) point, 7 x 2 x 2 = SGAP_NUM_POINTS of them,
+ * on the caller's operands with HIP events on `stream`, and reports the
+ * fastest.  Each point runs once, timed, as a warm-up and,
+ * unless that run was more than 4 times slower than the best point so far,
+ * `reps` more times (reps >= 1); its time is the minimum over its timed runs and
+ * includes the row-zeroing pass of the nnz-balanced schedule.
+ *   table  host, NULL or room for SGAP_NUM_POINTS entries, filled in the order
+ *          schedule (row-split first), strategy (parallel first), group size
+ *          ascending.
+ *   best   host, not NULL: the fastest point.
+ * The call blocks until the measurements are done (it synchronises `stream`),
+ * allocates no device memory and leaves in C the result of the fastest point,
+ * computed last.  M == 0 or N == 0: nothing to time, SGAP_ERR_INVALID_ARG.
+ * Other arguments and errors as for sgap_spmm_csr_ex.
+ */
+#define SGAP_NUM_POINTS 28
+typedef struct {
+    int group_size;
+    int strategy;
+    int schedule;
+    float ms;
+} sgap_point_time;
+int sgap_autotune_csr(int64_t M, int64_t K, int64_t N,
+                      const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                      const float* B, float* C, int64_t nnz_hint, int reps,
+                      sgap_point_time* table, sgap_point_time* best, void* stream);
+
 /* Text for a status code / detail of this thread's last failure (static or
  * thread-local storage; never free). */
 const char* sgap_status_string(int status);

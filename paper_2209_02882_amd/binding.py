@@ -25,6 +25,8 @@ SGAP_SCHED_NNZ_BALANCED = 1
 
 STRATEGIES = {"parallel": SGAP_REDUCE_PARALLEL, "serial": SGAP_REDUCE_SERIAL}
 SCHEDULES = {"row_split": SGAP_SCHED_ROW_SPLIT, "nnz_balanced": SGAP_SCHED_NNZ_BALANCED}
+STRATEGY_NAMES = {v: k for k, v in STRATEGIES.items()}
+SCHEDULE_NAMES = {v: k for k, v in SCHEDULES.items()}
 GROUP_SIZES = (1, 2, 4, 8, 16, 32, 64)
 
 # every symbol include/sgap.h declares: name -> (restype, argtypes)
@@ -35,6 +37,7 @@ EXPORTS = {
     "sgap_spmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_spmm_csr_ex": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
+    "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
@@ -177,6 +180,29 @@ def sgap_spmm_csr_gr(M, K, N, rowptr, colidx, vals, B, C, group_size, reduce_siz
         nnz_hint = colidx.numel()
     _check(load().sgap_spmm_csr_gr(M, K, N, *ptrs, int(group_size), int(reduce_size), int(nnz_hint),
                                    _stream_ptr(stream)))
+
+
+class PointTime(ctypes.Structure):
+    """Mirror of sgap_point_time."""
+    _fields_ = [("group_size", ctypes.c_int), ("strategy", ctypes.c_int), ("schedule", ctypes.c_int),
+                ("ms", ctypes.c_float)]
+
+
+SGAP_NUM_POINTS = 28
+
+
+def sgap_autotune_csr(M, K, N, rowptr, colidx, vals, B, C, nnz_hint=None, reps=3, stream=None):
+    """Time every design-space point on these operands (blocking).  Returns
+    (best, table): PointTime of the fastest point and the list of all 28."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    table = (PointTime * SGAP_NUM_POINTS)()
+    best = PointTime()
+    _check(load().sgap_autotune_csr(M, K, N, *ptrs, int(nnz_hint), int(reps),
+                                    ctypes.cast(table, ctypes.c_void_p), ctypes.cast(ctypes.pointer(best), ctypes.c_void_p),
+                                    _stream_ptr(stream)))
+    return best, list(table)
 
 
 def sgap_debug_group_partial_reduce(inp, out, group_size, reduce_size, lanes_per_row, stream=None) -> None:

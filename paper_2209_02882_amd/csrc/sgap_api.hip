@@ -276,6 +276,59 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, con
                      nnz_hint, stream, reduce_size);
 }
 
+int sgap_autotune_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                      const float* vals, const float* B, float* C, int64_t nnz_hint, int reps, sgap_point_time* table,
+                      sgap_point_time* best, void* stream)
+{
+    if (!best) return fail(SGAP_ERR_INVALID_ARG, "best must not be null");
+    if (reps < 1) return fail(SGAP_ERR_INVALID_ARG, "reps must be >= 1");
+    if (M <= 0 || N <= 0) return fail(SGAP_ERR_INVALID_ARG, "nothing to time: M and N must be positive");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) hipEventDestroy(e0);
+        return fail(SGAP_ERR_HIP, "could not create timing events");
+    }
+    int status = SGAP_OK;
+    // one timed run of a point; < 0 on error
+    auto timed = [&](const sgap_point_time& pt) -> float {
+        float ms = -1.0f;
+        if (hipEventRecord(e0, s) != hipSuccess) status = fail(SGAP_ERR_HIP, "event record failed");
+        if (status == SGAP_OK)
+            status = spmm_impl(M, K, N, rowptr, colidx, vals, B, C, pt.group_size, pt.strategy, pt.schedule, nnz_hint,
+                               stream);
+        if (status == SGAP_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                                  hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            status = fail(SGAP_ERR_HIP, "could not time a launch");
+        return status == SGAP_OK ? ms : -1.0f;
+    };
+    sgap_point_time fastest = {0, 0, 0, -1.0f};
+    int idx = 0;
+    for (int schedule : {SGAP_SCHED_ROW_SPLIT, SGAP_SCHED_NNZ_BALANCED}) {
+        for (int strategy : {SGAP_REDUCE_PARALLEL, SGAP_REDUCE_SERIAL}) {
+            for (int group = 1; group <= 64 && status == SGAP_OK; group *= 2, ++idx) {
+                sgap_point_time pt = {group, strategy, schedule, 0.0f};
+                pt.ms = timed(pt);
+                const bool hopeless = fastest.ms > 0.0f && pt.ms > 4.0f * fastest.ms;
+                for (int r = 0; r < reps && !hopeless && status == SGAP_OK; ++r) {
+                    const float ms = timed(pt);
+                    if (ms < pt.ms) pt.ms = ms;
+                }
+                if (status != SGAP_OK) break;
+                if (table) table[idx] = pt;
+                if (fastest.ms < 0.0f || pt.ms < fastest.ms) fastest = pt;
+            }
+        }
+    }
+    // leave the fastest point's result in C
+    if (status == SGAP_OK) timed(fastest);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (status != SGAP_OK) return status;
+    *best = fastest;
+    return SGAP_OK;
+}
+
 const char* sgap_status_string(int status)
 {
     switch (status) {

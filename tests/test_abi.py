@@ -71,6 +71,22 @@ def test_invalid_arguments_are_rejected_without_launch(kw, msg):
     assert msg in lib.sgap_last_error()
 
 
+def test_reduce_size_and_tuner_arguments_are_checked_without_launch():
+    lib = binding.load()
+    ptrs = (0x1000, 0x2000, 0x3000, 0x4000, 0x5000)
+    for g, r in [(8, 16), (8, 3), (8, 0), (8, -2), (3, 1)]:
+        assert lib.sgap_spmm_csr_gr(4, 4, 4, *ptrs, g, r, -1, None) == binding.SGAP_ERR_INVALID_ARG
+    best = binding.PointTime()
+    pbest = ctypes.cast(ctypes.pointer(best), ctypes.c_void_p)
+    assert lib.sgap_autotune_csr(4, 4, 4, *ptrs, -1, 3, None, None, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"best" in lib.sgap_last_error()
+    assert lib.sgap_autotune_csr(4, 4, 4, *ptrs, -1, 0, None, pbest, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"reps" in lib.sgap_last_error()
+    assert lib.sgap_autotune_csr(0, 4, 4, *ptrs, -1, 1, None, pbest, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, 300) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, 0) == 0
+
+
 def test_empty_shapes_are_ok_without_launch():
     lib = binding.load()
     assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0

@@ -342,6 +342,21 @@ def test_reduce_width_argument_checks():
             dp.launch_gr(C, g, r)
 
 
+def test_tuner_times_every_point_and_leaves_the_best_result():
+    p = wl.make_problem("powerlaw", scale_down=4)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    C = dp.new_output(poison=True)
+    best, table = binding.sgap_autotune_csr(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, reps=2)
+    torch.cuda.synchronize()
+    got = [(t.group_size, binding.STRATEGY_NAMES[t.strategy], binding.SCHEDULE_NAMES[t.schedule]) for t in table]
+    assert got == POINTS
+    assert all(t.ms > 0 for t in table)
+    assert best.ms == min(t.ms for t in table)
+    assert (best.group_size, best.strategy, best.schedule) in [(t.group_size, t.strategy, t.schedule) for t in table]
+    assert_close(C, C_ref, BND, what="result left by the tuner")
+
+
 @pytest.mark.parametrize("name", ["powerlaw", "rmat", "skewed"])
 def test_nnz_tile_sizes(name):
     # every tile size of the nnz-balanced serial kernel, on inputs with rows
