@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--point", default=None, help="fix the point: e.g. 8,parallel,row_split (skips the sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-out", default=None, help="write the per-point sweep table (JSON) to this file")
+    ap.add_argument("--gr", action="store_true",
+                    help="also sweep the row-split points with the reduction narrower than the tiling "
+                         "(group_size lanes per row, sub-groups of reduce_size < group_size merged with atomics)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
@@ -137,6 +140,20 @@ def main():
                 f"{flops / t / 1e9:9.1f} GFLOP/s {min_bytes / t / 1e9:8.1f} GB/s")
         b = min(sweep, key=lambda r: r["ms"])
         best = (b["group"], b["strategy"], b["schedule"])
+    gr_sweep = []
+    if a.gr:
+        from paper_2209_02882_amd.device import GR_POINTS
+
+        for g_lanes, r_lanes in GR_POINTS:
+            dp.launch_gr(C, g_lanes, r_lanes)  # warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(a.sweep_iters):
+                dp.launch_gr(C, g_lanes, r_lanes)
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / a.sweep_iters
+            gr_sweep.append({"group": g_lanes, "reduce": r_lanes, "ms": t * 1e3})
+            log(f"[sweep] row_split parallel g={g_lanes:2d} r={r_lanes:2d} {t * 1e3:9.3f} ms")
     log(f"[bench] timing point {best}")
 
     g, st, sc = best
@@ -203,7 +220,8 @@ def main():
         out["cpu_baseline"] = cpu_baseline(p)
     if a.sweep_out and sweep:
         with open(a.sweep_out, "w") as f:
-            json.dump({"workload": a.workload, "stats": p.row_stats(), "points": sweep}, f, indent=1)
+            json.dump({"workload": a.workload, "stats": p.row_stats(), "points": sweep, "gr_points": gr_sweep}, f,
+                      indent=1)
     print(json.dumps(out), flush=True)
 
 

@@ -49,8 +49,32 @@ __device__ __forceinline__ void gather_batch(Vec<VEC>& acc, const StagedEntry* _
     for (int j = 0; j < U; ++j) acc.fma(e[j].val, b[j]);
 }
 
+// The last 1..U entries q, q+STRIDE, ... < q1 as one batch: entries past q1
+// load nothing and contribute +0.
+template <int VEC, int STRIDE, int U, typename SRC>
+__device__ __forceinline__ void gather_tail(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q,
+                                            uint32_t q1, const SRC& B)
+{
+    StagedEntry e[U];
+    Vec<VEC> b[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        e[j].col = 0;
+        e[j].val = 0.0f;
+        if (q + j * STRIDE < q1) e[j] = s_A[q + j * STRIDE];
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        b[j].zero();
+        if (q + j * STRIDE < q1) b[j] = B.load(e[j].col);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) acc.fma(e[j].val, b[j]);
+}
+
 // acc += sum over LDS slots q = q0, q0+STRIDE, ... < q1 of val[q] * B[col[q], k..k+VEC)
-// Full batches of 8, then the remainder as batches of 4, 2 and 1.
+// Full batches of 8, then the remaining 1..7 entries as one more round of
+// loads (of 4 or 8 slots), so that a row costs ceil(len/8) memory round trips.
 template <int VEC, int STRIDE, typename SRC>
 __device__ __forceinline__ void gather_fma(Vec<VEC>& acc, const StagedEntry* __restrict__ s_A, uint32_t q0,
                                            uint32_t q1, const SRC& B)
@@ -58,16 +82,8 @@ __device__ __forceinline__ void gather_fma(Vec<VEC>& acc, const StagedEntry* __r
     uint32_t q = q0;
     for (; q + 7 * STRIDE < q1; q += 8 * STRIDE) gather_batch<VEC, STRIDE, 8>(acc, s_A, q, B);
     if (q >= q1) return;
-    const uint32_t left = (q1 - q + STRIDE - 1) / STRIDE;  // 1..7
-    if (left & 4) {
-        gather_batch<VEC, STRIDE, 4>(acc, s_A, q, B);
-        q += 4 * STRIDE;
-    }
-    if (left & 2) {
-        gather_batch<VEC, STRIDE, 2>(acc, s_A, q, B);
-        q += 2 * STRIDE;
-    }
-    if (left & 1) gather_batch<VEC, STRIDE, 1>(acc, s_A, q, B);
+    if (q + 4 * STRIDE < q1) gather_tail<VEC, STRIDE, 8>(acc, s_A, q, q1, B);
+    else gather_tail<VEC, STRIDE, 4>(acc, s_A, q, q1, B);
 }
 
 }  // namespace sgap
