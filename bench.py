@@ -27,10 +27,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # scaled by the same counters on the library's plain copy kernel; keyed by
 # (workload, group, strategy, schedule).  See profiles/ for the runs.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("stencil27", 1, "parallel", "row_split"): 2_272_718_950,   # profiles/row_split_kernel_stencil27.md
-    ("stencil27", 1, "serial", "row_split"): 2_260_543_553,     # profiles/row_split_kernel_stencil27_serial.md
-    ("rmat", 32, "serial", "nnz_balanced"): 4_488_105_763,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
-    ("skewed", 64, "serial", "nnz_balanced"): 59_931_994_186,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
+    ("stencil27", 1, "parallel", "row_split"): 2_273_828_282,   # profiles/row_split_kernel_stencil27.md
+    ("stencil27", 1, "serial", "row_split"): 2_260_637_744,     # profiles/row_split_kernel_stencil27_serial.md
+    ("rmat", 32, "serial", "nnz_balanced"): 4_488_103_167,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
+    ("skewed", 64, "serial", "nnz_balanced"): 59_931_999_089,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
+    ("powerlaw", 16, "serial", "nnz_balanced"): 243_223_740,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
 }
 
 
