@@ -1,9 +1,10 @@
-"""CPU oracle for CSR SpMM (test infrastructure, not part of the product).
+"""CPU oracles for CSR SpMM and CSR SDDMM (test infrastructure, not part of
+the product).
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import
-this package.  It wraps `spmm_oracle.c` (plain C, fp64, row by row; see that
-file's header for what it follows in the paper and what pins it) via ctypes
-and never touches the HIP library.
+this package.  It wraps `spmm_oracle.c` and `sddmm_oracle.c` (plain C, fp64,
+row by row; see those files' headers for what they follow in the paper and
+what pins them) via ctypes and never touches the HIP library.
 """
 from __future__ import annotations
 
@@ -14,16 +15,16 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "spmm_oracle.c")
+_SRCS = [os.path.join(_HERE, "spmm_oracle.c"), os.path.join(_HERE, "sddmm_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle_spmm.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (plain -O2, OpenMP for the row split)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               _SRC, "-o", _LIB, "-lm"]
+               *_SRCS, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -39,6 +40,8 @@ def _load():
         lib.oracle_spmm_csr.restype = ctypes.c_int
         lib.oracle_spmm_csr_rows.argtypes = [i64, i64, i64, p, p, p, p, p, i64, p, p]
         lib.oracle_spmm_csr_rows.restype = ctypes.c_int
+        lib.oracle_sddmm_csr.argtypes = [i64, i64, i64, p, p, p, p, p, p, p, ctypes.c_int]
+        lib.oracle_sddmm_csr.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -87,3 +90,21 @@ def spmm_csr_rows(M, K, N, rowptr, colidx, vals, B, rows):
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return C, BND
+
+
+def sddmm_csr(M, K, J, rowptr, colidx, vals, X1, X2T, nthreads: int = 1, bound: bool = True):
+    """out[p] = vals[p] * <X1[row(p), :], X2T[colidx[p], :]> for every stored
+    entry p.  Returns (out_ref, BND) as float64 arrays of rowptr[M] entries."""
+    rowptr, colidx, vals, X2T = _check_inputs(M, K, J, rowptr, colidx, vals, X2T)
+    X1 = np.ascontiguousarray(X1, dtype=np.float32)
+    if X1.size != M * J:
+        raise ValueError("X1 must be M x J")
+    nnz = colidx.size
+    out = np.empty(nnz, dtype=np.float64)
+    BND = np.empty(nnz, dtype=np.float64) if bound else None
+    rc = _load().oracle_sddmm_csr(
+        M, K, J, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data, X1.ctypes.data, X2T.ctypes.data,
+        out.ctypes.data, BND.ctypes.data if bound else None, int(nthreads))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out, BND
