@@ -145,6 +145,36 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N,
                      int group_size, int reduce_size, int64_t nnz_hint, void* stream);
 
 /*
+ * Sampled dense-dense matrix product on the pattern of a CSR matrix, the
+ * SDDMM form of the paper's Section 2.1 (third form under Eq. 1):
+ *   out_vals[p] = vals[p] * sum_{j<J} X1[row(p), j] * X2T[colidx[p], j]
+ * for every stored entry p of A (M x K, CSR as for sgap_spmm_csr; row(p) is
+ * the row whose rowptr range holds p).  The paper names it next to SpMM
+ * because its reduction, here along the dense dimension j, is served by the
+ * same segment-group reductions.
+ *   X1        device, M x J row-major, ld = J
+ *   X2T       device, K x J row-major, ld = J: the second dense operand
+ *             transposed, X2T[k, j] = X2[j, k], so that both factors of an
+ *             entry are contiguous rows
+ *   out_vals  device, rowptr[M] values in the order of colidx; OVERWRITTEN.
+ *             May not alias vals.
+ *   group_size, strategy
+ *             SGAP_REDUCE_PARALLEL: group_size lanes share a stored entry,
+ *             split j between them and tree-sum; SGAP_REDUCE_SERIAL: every
+ *             lane computes group_size consecutive stored entries by itself.
+ *   nnz_hint  rowptr[M] if the host knows it, else -1 (sizes the grid; 0
+ *             returns at once).
+ * Every output has one writer: no atomics, results are reproducible run to
+ * run.  Asynchronous on `stream`; ownership and errors as for sgap_spmm_csr.
+ * J == 0 writes zeros.  colidx, vals and out_vals may be null only for a
+ * matrix without stored entries.
+ */
+int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J,
+                   const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                   const float* X1, const float* X2T, float* out_vals,
+                   int group_size, int strategy, int64_t nnz_hint, void* stream);
+
+/*
  * Tuner over the design space: the paper closes (Section 8) by proposing that
  * the space be exposed as an auto-tuning interface, and Table 5 measures what
  * a per-matrix choice gains over the best fixed point.  Times every

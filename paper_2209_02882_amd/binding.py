@@ -38,6 +38,7 @@ EXPORTS = {
     "sgap_spmm_csr_ex": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
     "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
+    "sgap_sddmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
@@ -180,6 +181,26 @@ def sgap_spmm_csr_gr(M, K, N, rowptr, colidx, vals, B, C, group_size, reduce_siz
         nnz_hint = colidx.numel()
     _check(load().sgap_spmm_csr_gr(M, K, N, *ptrs, int(group_size), int(reduce_size), int(nnz_hint),
                                    _stream_ptr(stream)))
+
+
+def sgap_sddmm_csr(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size, strategy, nnz_hint=None,
+                   stream=None) -> None:
+    """out_vals[p] = vals[p] * <X1[row(p), :], X2T[colidx[p], :]> (see include/sgap.h)."""
+    import torch
+
+    if rowptr.numel() != M + 1:
+        raise ValueError("rowptr must have M+1 entries")
+    if colidx.numel() != vals.numel() or out_vals.numel() != vals.numel():
+        raise ValueError("colidx, vals and out_vals must have the same length")
+    if X1.numel() != M * J or X2T.numel() != K * J:
+        raise ValueError("X1 must hold M*J and X2T must hold K*J elements")
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    _check(load().sgap_sddmm_csr(
+        M, K, J, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+        _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"),
+        _dev_ptr(X2T, torch.float32, "X2T"), _dev_ptr(out_vals, torch.float32, "out_vals"),
+        int(group_size), int(strategy), int(nnz_hint), _stream_ptr(stream)))
 
 
 class PointTime(ctypes.Structure):

@@ -276,6 +276,54 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, con
                      nnz_hint, stream, reduce_size);
 }
 
+int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                   const float* X1, const float* X2T, float* out_vals, int group_size, int strategy, int64_t nnz_hint,
+                   void* stream)
+{
+    using namespace sgap;
+    if (M < 0 || K < 0 || J < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
+    if (M > 2147483646LL || J > 2147483647LL || K > 2147483647LL)
+        return fail(SGAP_ERR_INVALID_ARG, "dimension exceeds int32 index range");
+    if (!is_pow2_group(group_size)) return fail(SGAP_ERR_INVALID_ARG, "group_size must be 1,2,4,8,16,32 or 64");
+    if (strategy != SGAP_REDUCE_PARALLEL && strategy != SGAP_REDUCE_SERIAL)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
+    if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
+    if (M == 0 || nnz_hint == 0) return SGAP_OK;
+    if (!rowptr) return fail(SGAP_ERR_INVALID_ARG, "rowptr must not be null");
+    if (!colidx || !vals || !out_vals) {
+        // arrays of no entries may be null; a matrix with entries cannot come without them
+        if (nnz_hint > 0) return fail(SGAP_ERR_INVALID_ARG, "colidx, vals and out_vals must not be null when A has entries");
+        return SGAP_OK;
+    }
+    if (J > 0 && (!X1 || !X2T)) return fail(SGAP_ERR_INVALID_ARG, "X1 and X2T must not be null when J > 0");
+
+    const uintptr_t align_bits = reinterpret_cast<uintptr_t>(X1) | reinterpret_cast<uintptr_t>(X2T);
+    int vec = 1;
+    if (J % 4 == 0 && (align_bits & 15) == 0) vec = 4;
+    else if (J % 2 == 0 && (align_bits & 7) == 0) vec = 2;
+
+    SpmmArgs a;
+    a.M = M; a.K = K; a.N = J;
+    a.rowptr = rowptr; a.colidx = colidx; a.vals = vals; a.B = X2T; a.C = nullptr;
+    a.group = group_size;
+    a.log2_group = ilog2(group_size);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    auto mark = [&](hipEvent_t& ev) {
+        if (g_profile && hipEventCreate(&ev) == hipSuccess) hipEventRecord(ev, s);
+    };
+    mark(ev0);
+    const bool par = strategy == SGAP_REDUCE_PARALLEL;
+    hipError_t err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, compute_units(),
+                                  nnz_hint, s);
+    if (ev0) {
+        mark(ev1);
+        if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);
+    }
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
 int sgap_autotune_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
                       const float* vals, const float* B, float* C, int64_t nnz_hint, int reps, sgap_point_time* table,
                       sgap_point_time* best, void* stream)

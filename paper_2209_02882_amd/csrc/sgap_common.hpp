@@ -178,6 +178,11 @@ hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, const NnzPlan& 
                              int64_t nnz_hint, hipStream_t s);
 // r = members per reducing sub-group (r = g: the whole group)
 hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, int lc, hipStream_t s);
+// Sampled dense-dense product on A's pattern: a carries M, K, N = J, rowptr,
+// colidx, vals and B = X2T (K x J); X1 is M x J; out has one value per stored
+// entry.  g lanes per entry (per_lane = 0) or one lane per per_lane entries.
+hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec,
+                        int compute_units, int64_t nnz_hint, hipStream_t stream);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s);

@@ -1,0 +1,216 @@
+// Sampled dense-dense matrix product on the pattern of a CSR matrix
+// (Section 2.1, the SDDMM form under Eq. 1):
+//     out[p] = vals[p] * sum_{j<J} X1[row(p), j] * X2T[colidx[p], j]
+// The paper's point in naming this operator next to SpMM is that the
+// reduction is the same kind of object in both (Section 2.1: here it runs
+// along the dense dimension j), so the same segment-group primitives serve:
+//   parallel  G lanes share one stored entry, each takes every G-th chunk of
+//             c columns of the two dense rows, the group tree-sums
+//             (group_tree_sum, the library's atomicAddGroup) and its first
+//             lane writes the entry: {<1 nnz, 1/g col>, g} in the notation of
+//             Section 3.3 with the dense dimension split instead of a row.
+//   serial    r = 1: a lane walks group_size consecutive stored entries by
+//             itself, whole dot products in its own register.
+// Every output has exactly one writer: no atomics, no zeroing.
+//
+// The unit of work is a stored entry, so the schedule is nnz-balanced by
+// construction: tiles of 1024 entries are dealt round-robin to persistent
+// workgroups, the rows of a tile's entries come from a bisection of rowptr
+// for the tile's first entry and an LDS window of rowptr for the rest (the
+// same pieces as the nnz-balanced SpMM kernels).
+#include "sgap_common.hpp"
+#include "sgap_lane_ops.hpp"
+#include "sgap_nnz_common.hpp"
+
+namespace sgap {
+
+constexpr int kSddmmTile = 1024;   // stored entries per tile
+constexpr int kSddmmDepth = 4;     // entries (parallel) or column chunks (serial) in flight per lane
+
+struct SddmmArgs {
+    SpmmArgs a;       // M, K, N = J, rowptr, colidx, vals; B = X2T; C unused
+    const float* __restrict__ X1;
+    float* __restrict__ out;
+};
+
+template <int VEC>
+__device__ __forceinline__ float dot_vec(const Vec<VEC>& x, const Vec<VEC>& y, float acc)
+{
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc = __builtin_fmaf(x.v[i], y.v[i], acc);
+    return acc;
+}
+
+// per_lane = 0: parallel strategy, G lanes per entry.  per_lane > 0 (G = 1):
+// serial strategy, per_lane consecutive entries per lane.
+template <int G, int VEC>
+__global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane)
+{
+    __shared__ int32_t s_col[kSddmmTile];
+    __shared__ float s_val[kSddmmTile];
+    __shared__ int32_t s_row[kSddmmTile];
+    __shared__ int32_t s_win[kWindowCap + 1];
+    __shared__ int32_t s_tile_row[kTileRowBatch];
+    constexpr int SLOTS = kBlock / G;
+
+    const SpmmArgs& a = s.a;
+    const int tid = threadIdx.x;
+    const int slot = tid / G;
+    const int member = tid % G;
+    const int64_t J = a.N;
+    const float* __restrict__ X2T = a.B;
+    const int32_t nnz = a.rowptr[a.M];
+    const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
+    if ((int64_t)blockIdx.x >= tiles) return;
+    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+
+    for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
+        find_tile_rows(a, j0, my_tiles, kSddmmTile, s_tile_row);
+        const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
+        for (int64_t j = j0; j < j1; ++j) {
+            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int32_t tile_start = (int32_t)(t * kSddmmTile);
+            const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
+            const int cnt = tile_end - tile_start;
+            int32_t row_lb = s_tile_row[j - j0];
+
+            __syncthreads();  // the previous tile is consumed
+            for (int i = tid; i < cnt; i += kBlock) {
+                s_col[i] = load_stream(a.colidx + tile_start + i);
+                s_val[i] = load_stream(a.vals + tile_start + i);
+            }
+            // the row of every entry, through the rowptr window (cut at row
+            // boundaries where long runs of empty rows overflow it)
+            for (int32_t base = tile_start; base < tile_end;) {
+                __syncthreads();
+                const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
+                for (int i = tid; i < w.cnt; i += kBlock)
+                    s_row[base - tile_start + i] =
+                        row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
+                row_lb += w.n_last;
+                base += w.cnt;
+            }
+            __syncthreads();
+
+            if (per_lane == 0) {
+                // U entries per group at a time, so that 2*U rows are in flight
+                constexpr int U = kSddmmDepth;
+                for (int e0 = 0; e0 < cnt; e0 += U * SLOTS) {  // same trip count in every lane
+                    float acc[U];
+                    const float* x1p[U];
+                    const float* x2p[U];
+                    bool ok[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int e = e0 + u * SLOTS + slot;
+                        ok[u] = e < cnt;
+                        const int32_t row = ok[u] ? s_row[e] : 0;
+                        const int32_t col = ok[u] ? s_col[e] : 0;
+                        x1p[u] = s.X1 + (int64_t)row * J;
+                        x2p[u] = X2T + (int64_t)col * J;
+                        acc[u] = 0.0f;
+                    }
+                    for (int64_t c = (int64_t)member * VEC; c < J; c += (int64_t)G * VEC) {
+                        Vec<VEC> x1[U], x2[U];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            x1[u].zero();
+                            x2[u].zero();
+                            if (ok[u]) {
+                                x1[u] = load_vec<VEC>(x1p[u] + c);
+                                x2[u] = load_vec<VEC>(x2p[u] + c);
+                            }
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) acc[u] = dot_vec<VEC>(x1[u], x2[u], acc[u]);
+                    }
+                    // members past the end of the dense rows contributed +0 (zero extension)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) acc[u] = group_tree_sum<G, 1>(acc[u]);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int e = e0 + u * SLOTS + slot;
+                        if (member == 0 && ok[u]) s.out[tile_start + e] = s_val[e] * acc[u];
+                    }
+                }
+            } else if constexpr (G == 1) {
+                constexpr int U = kSddmmDepth;
+                for (int i = 0; i < per_lane; ++i) {
+                    for (int e = (tid * per_lane + i); e < cnt; e += kBlock * per_lane) {
+                        const float* __restrict__ x1p = s.X1 + (int64_t)s_row[e] * J;
+                        const float* __restrict__ x2p = X2T + (int64_t)s_col[e] * J;
+                        float acc = 0.0f;
+                        int64_t c = 0;
+                        for (; c + U * VEC <= J; c += U * VEC) {
+                            Vec<VEC> x1[U], x2[U];
+#pragma unroll
+                            for (int u = 0; u < U; ++u) {
+                                x1[u] = load_vec<VEC>(x1p + c + u * VEC);
+                                x2[u] = load_vec<VEC>(x2p + c + u * VEC);
+                            }
+#pragma unroll
+                            for (int u = 0; u < U; ++u) acc = dot_vec<VEC>(x1[u], x2[u], acc);
+                        }
+                        for (; c < J; c += VEC) acc = dot_vec<VEC>(load_vec<VEC>(x1p + c), load_vec<VEC>(x2p + c), acc);
+                        s.out[tile_start + e] = s_val[e] * acc;
+                    }
+                }
+            }
+        }
+    }
+}
+
+namespace {
+
+template <int G, int VEC>
+void launch_one(const SddmmArgs& s, int per_lane, int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    static const int per_cu = resident_per_cu(sddmm_kernel<G, VEC>, 0);
+    const int grid = persistent_grid(per_cu, compute_units, nnz_hint, kSddmmTile);
+    hipLaunchKernelGGL((sddmm_kernel<G, VEC>), dim3(grid), dim3(kBlock), 0, stream, s, per_lane);
+}
+
+template <int G>
+bool launch_vec(const SddmmArgs& s, int vec, int per_lane, int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    switch (vec) {
+        case 4: launch_one<G, 4>(s, per_lane, compute_units, nnz_hint, stream); return true;
+        case 2: launch_one<G, 2>(s, per_lane, compute_units, nnz_hint, stream); return true;
+        case 1: launch_one<G, 1>(s, per_lane, compute_units, nnz_hint, stream); return true;
+        default: return false;
+    }
+}
+
+}  // namespace
+
+// a: M, K, N = J, rowptr, colidx, vals, B = X2T (C unused).  g = lanes per
+// stored entry (parallel strategy, per_lane = 0) or 1 with per_lane = entries
+// per lane (serial strategy).  vec = columns per lane and load (4, 2 or 1;
+// J % vec == 0 and matching alignment of X1 and X2T).
+hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec,
+                        int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    SddmmArgs s;
+    s.a = a;
+    s.X1 = X1;
+    s.out = out;
+    bool ok = false;
+    if (per_lane > 0) {
+        ok = launch_vec<1>(s, vec, per_lane, compute_units, nnz_hint, stream);
+    } else {
+        switch (g) {
+            case 1: ok = launch_vec<1>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 2: ok = launch_vec<2>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 4: ok = launch_vec<4>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 8: ok = launch_vec<8>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 16: ok = launch_vec<16>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 32: ok = launch_vec<32>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            case 64: ok = launch_vec<64>(s, vec, 0, compute_units, nnz_hint, stream); break;
+            default: break;
+        }
+    }
+    if (!ok) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace sgap

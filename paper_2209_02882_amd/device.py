@@ -49,6 +49,21 @@ class DeviceProblem:
         torch.cuda.synchronize()
         return C
 
+    def launch_sddmm(self, X1, out, group, strategy, nnz_hint=None, stream=None):
+        """Enqueue out[p] = vals[p] * <X1[row(p)], B[colidx[p]]> (B serves as the
+        transposed second dense operand); asynchronous."""
+        p = self.p
+        binding.sgap_sddmm_csr(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, X1, self.B, out,
+                               group, binding.STRATEGIES[strategy], nnz_hint=nnz_hint, stream=stream)
+
+    def run_sddmm(self, X1, group, strategy, poison=True):
+        out = torch.empty(self.p.nnz, dtype=torch.float32, device=self.rowptr.device)
+        if poison:
+            out.fill_(float("nan"))
+        self.launch_sddmm(X1, out, group, strategy)
+        torch.cuda.synchronize()
+        return out
+
     def run(self, group, strategy, schedule, poison=True, C=None, nnz_hint=None):
         """Run one point to completion; by default C starts filled with NaN so
         that any element the kernels fail to write is visible."""

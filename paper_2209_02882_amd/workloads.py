@@ -283,3 +283,17 @@ def make_problem(name: str, N: int | None = None, scale_down: int = 1) -> SpmmPr
     vals = fill_values(rng, int(rowptr[-1]), integer)
     B = dense_operand(seed + 100, K, N, integer)
     return SpmmProblem(name, M, K, N, rowptr, colidx, vals, B)
+
+
+def sddmm_left_operand(p: SpmmProblem, integer: bool | None = None) -> np.ndarray:
+    """The M x J dense operand X1 of an SDDMM on problem p's pattern (J = p.N;
+    the K x J operand X2T is p.B).  Seeded per workload (seed + 200)."""
+    seed, _ = WORKLOADS[p.name]
+    if integer is None:
+        integer = p.name.endswith("_int")
+    return dense_operand(seed + 200, p.M, p.N, integer)
+
+
+def sddmm_minimal_bytes(p: SpmmProblem) -> int:
+    """colidx, vals read once, out written once, rowptr, X1 and X2T read once."""
+    return p.nnz * 12 + (p.M + 1) * 4 + p.M * p.N * 4 + p.K * p.N * 4

@@ -87,6 +87,24 @@ def test_reduce_size_and_tuner_arguments_are_checked_without_launch():
     assert lib.sgap_set_tuning(binding.SGAP_TUNE_NNZ_TILE, 0) == 0
 
 
+def test_sddmm_arguments_are_checked_without_launch():
+    lib = binding.load()
+    ok = dict(M=4, K=4, J=4, rowptr=0x1000, colidx=0x2000, vals=0x3000, X1=0x4000, X2T=0x5000, out=0x6000,
+              group=8, strategy=0, nnz_hint=-1)
+    for kw, msg in [(dict(M=-1), b"negative"), (dict(J=-2), b"negative"), (dict(group=3), b"group_size"),
+                    (dict(strategy=5), b"strategy"), (dict(nnz_hint=-7), b"nnz_hint"), (dict(rowptr=None), b"null"),
+                    (dict(out=None, nnz_hint=5), b"null"), (dict(X1=None), b"null"), (dict(X2T=None), b"null")]:
+        a = dict(ok)
+        a.update(kw)
+        rc = lib.sgap_sddmm_csr(a["M"], a["K"], a["J"], a["rowptr"], a["colidx"], a["vals"], a["X1"], a["X2T"],
+                                a["out"], a["group"], a["strategy"], a["nnz_hint"], None)
+        assert rc == binding.SGAP_ERR_INVALID_ARG, kw
+        assert msg in lib.sgap_last_error(), kw
+    # nothing to do: no rows, or no stored entries
+    assert lib.sgap_sddmm_csr(0, 4, 4, None, None, None, None, None, None, 8, 0, -1, None) == 0
+    assert lib.sgap_sddmm_csr(4, 4, 4, None, None, None, None, None, None, 8, 1, 0, None) == 0
+
+
 def test_empty_shapes_are_ok_without_launch():
     lib = binding.load()
     assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0
