@@ -35,6 +35,10 @@ MEASURED_TRAFFIC_BYTES: dict = {
 }
 
 
+# the same for --op sddmm, keyed by (workload, group, strategy)
+MEASURED_SDDMM_TRAFFIC_BYTES: dict = {}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -88,8 +92,127 @@ def cpu_baseline(p):
     }
 
 
+def sddmm_cpu_baseline(p, X1):
+    """The SDDMM oracle on all host cores, whole workload, repeated for about 10 s."""
+    import oracle
+
+    cores = len(os.sched_getaffinity(0))
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env))
+    reps, t_all = 0, 0.0
+    while t_all < 10.0 and reps < 200:
+        t0 = time.perf_counter()
+        oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=cores)
+        t_all += time.perf_counter() - t0
+        reps += 1
+    return {
+        "value": 2.0 * p.nnz * p.N * reps / t_all / 1e9,
+        "unit": "GFLOP/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"whole {p.name} workload x{reps}, fp64 entry-by-entry SDDMM oracle (result and error bound), "
+                  f"static row split over {cores} threads, {t_all:.1f} s",
+        "seconds_per_pass": t_all / reps,
+    }
+
+
+def main_sddmm(a):
+    """--op sddmm: the sampled dense-dense product on the workload's pattern
+    (J = the workload's N, X2T = its B, X1 seeded), same JSON contract."""
+    import torch
+
+    from paper_2209_02882_amd import binding
+    from paper_2209_02882_amd import workloads as wl
+    from paper_2209_02882_amd.device import DeviceProblem
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.load()
+    p = wl.make_problem(a.workload, N=a.ncols)
+    X1h = wl.sddmm_left_operand(p)
+    log(f"[bench] sddmm on {a.workload}: {p.row_stats()}")
+    dp = DeviceProblem(p)
+    X1 = torch.from_numpy(X1h).cuda()
+    out_vals = torch.empty(p.nnz, dtype=torch.float32, device="cuda:0")
+    min_bytes = wl.sddmm_minimal_bytes(p)
+    flops = 2 * p.nnz * p.N
+
+    def run(g, st, n):
+        for _ in range(n):
+            dp.launch_sddmm(X1, out_vals, g, st)
+
+    sweep = []
+    if a.point:
+        g, st = a.point.split(",")[:2]
+        best = (int(g), st)
+    else:
+        for st in ("parallel", "serial"):
+            for g in binding.GROUP_SIZES:
+                run(g, st, 1)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                run(g, st, a.sweep_iters)
+                torch.cuda.synchronize()
+                t = (time.perf_counter() - t0) / a.sweep_iters
+                sweep.append({"group": g, "strategy": st, "ms": t * 1e3, "gflops": flops / t / 1e9,
+                              "gbs": min_bytes / t / 1e9, "hbm_frac": min_bytes / t / 1e9 / HBM_PEAK_GBS})
+                log(f"[sweep] sddmm g={g:2d} {st:8s} {t * 1e3:9.3f} ms {flops / t / 1e9:9.1f} GFLOP/s "
+                    f"{min_bytes / t / 1e9:8.1f} GB/s")
+        b = min(sweep, key=lambda r: r["ms"])
+        best = (b["group"], b["strategy"])
+    g, st = best
+    run(g, st, a.warmup)
+    binding.sgap_profile_enable(True)
+    binding.sgap_profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(g, st, a.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, n_ev = binding.sgap_profile_collect()
+    binding.sgap_profile_enable(False)
+    ms_per_step = elapsed / a.steps * 1e3
+    kernel_avg_ms = kernel_ms / max(1, n_ev)
+    achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "SDDMM effective GFLOP/s (2*nnz*J/t), fp32, best (group_size, strategy) point",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": a.workload, "op": "sddmm", "M": p.M, "K": p.K, "J": p.N, "nnz": p.nnz,
+                   "group_size": g, "strategy": st},
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st)),
+            "kernel_avg_ms": kernel_avg_ms,
+            "algorithmic_bytes": min_bytes,
+        },
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = sddmm_cpu_baseline(p, X1h)
+    if a.sweep_out and sweep:
+        with open(a.sweep_out, "w") as f:
+            json.dump({"workload": a.workload, "op": "sddmm", "stats": p.row_stats(), "points": sweep}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm"),
+                    help="spmm (the headline path) or sddmm on the same workload's pattern")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
@@ -106,6 +229,9 @@ def main():
     if a.gpus != 1:
         sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
                  "(the path shards by row blocks without any exchange, see DESIGN.md)")
+
+    if a.op == "sddmm":
+        return main_sddmm(a)
 
     import torch
 

@@ -236,13 +236,19 @@ int sgap_version(void);
  *                        need N % 4 == 0 and 16-byte aligned B and C, else
  *                        the automatic choice is kept); 0 = automatic, from
  *                        nnz and the size of the chip.
+ *   SGAP_TUNE_SDDMM_ROW_CACHE  1 (default): sgap_sddmm_csr's parallel strategy
+ *                        hands a group consecutive stored entries and keeps
+ *                        the current row of X1 in registers when
+ *                        J <= 16 * group_size and the operands are 16-byte
+ *                        aligned; 0: every entry loads both of its rows.
  */
 typedef enum {
     SGAP_TUNE_TILE_COLS = 0,
     SGAP_TUNE_XCD_REMAP = 1,
     SGAP_TUNE_ROWS_PER_GROUP = 2,
     SGAP_TUNE_PERSISTENT = 3,
-    SGAP_TUNE_NNZ_TILE = 4
+    SGAP_TUNE_NNZ_TILE = 4,
+    SGAP_TUNE_SDDMM_ROW_CACHE = 5
 } sgap_tuning_knob;
 int sgap_set_tuning(int knob, int value);
 

@@ -154,6 +154,7 @@ SGAP_TUNE_XCD_REMAP = 1
 SGAP_TUNE_ROWS_PER_GROUP = 2
 SGAP_TUNE_PERSISTENT = 3
 SGAP_TUNE_NNZ_TILE = 4
+SGAP_TUNE_SDDMM_ROW_CACHE = 5
 
 
 def sgap_set_tuning(knob: int, value: int) -> None:

@@ -96,6 +96,7 @@ thread_local char t_last_error[256] = "";
 int g_tile_cols = 0;
 int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
 int g_rows_per_slot = 0;
+int g_sddmm_row_cache = 1;  // SDDMM parallel: keep rows of X1 in registers where the shape allows
 int g_nnz_tile = 0;    // nnz-balanced serial: forced tile size, 0 = automatic
 int g_persistent = 0;  // row-split: one workgroup per item keeps the rows in flight on a die close together
 
@@ -314,7 +315,7 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     };
     mark(ev0);
     const bool par = strategy == SGAP_REDUCE_PARALLEL;
-    hipError_t err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, compute_units(),
+    hipError_t err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, g_sddmm_row_cache != 0, compute_units(),
                                   nnz_hint, s);
     if (ev0) {
         mark(ev1);
@@ -405,6 +406,9 @@ int sgap_set_tuning(int knob, int value)
             return SGAP_OK;
         case SGAP_TUNE_PERSISTENT:
             g_persistent = value != 0;
+            return SGAP_OK;
+        case SGAP_TUNE_SDDMM_ROW_CACHE:
+            g_sddmm_row_cache = value != 0;
             return SGAP_OK;
         case SGAP_TUNE_NNZ_TILE:
             if (value != 0 && value != 256 && value != 512 && value != 1024 && value != 2048)

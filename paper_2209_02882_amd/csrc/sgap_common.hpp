@@ -181,7 +181,8 @@ hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, 
 // Sampled dense-dense product on A's pattern: a carries M, K, N = J, rowptr,
 // colidx, vals and B = X2T (K x J); X1 is M x J; out has one value per stored
 // entry.  g lanes per entry (per_lane = 0) or one lane per per_lane entries.
-hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec,
+// row_cache lets the parallel strategy keep rows of X1 in registers where the shape allows.
+hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec, bool row_cache,
                         int compute_units, int64_t nnz_hint, hipStream_t stream);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);

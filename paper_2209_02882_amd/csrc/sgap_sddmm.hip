@@ -160,7 +160,143 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
     }
 }
 
+// Parallel strategy when the G lanes of a group cover a dense row in S <= 4
+// steps of 4 columns each (J <= S*G*4, 16-byte aligned operands).
+// A group takes its stored entries in batches of U CONSECUTIVE ones, which
+// mostly belong to one row of A, and keeps that row's chunk of X1 in
+// registers: a row of X1 is loaded when the row changes, not once per entry,
+// which takes up to half of the volume off the vector memory path.  The
+// batches of a round are dealt to the groups in order, so that the workgroup
+// as a whole still moves through neighbouring entries, whose rows of X2T tend
+// to be neighbours or the same (L1 hits).  The loads of a batch (rows of X2T,
+// and rows of X1 where the row changes inside the batch) are issued together.
+template <int G, int S>
+__global__ __launch_bounds__(kBlock) void sddmm_rowcache_kernel(SddmmArgs s)
+{
+    constexpr int VEC = 4;
+    constexpr int SLOTS = kBlock / G;
+    constexpr int EPS = kSddmmTile / SLOTS;  // entries per group and tile
+    constexpr int U = 8 / S < EPS ? 8 / S : EPS;  // entries per batch: U*S <= 8 loads per operand in flight
+    __shared__ int32_t s_col[kSddmmTile];
+    __shared__ float s_val[kSddmmTile];
+    __shared__ int32_t s_row[kSddmmTile];
+    __shared__ int32_t s_win[kWindowCap + 1];
+    __shared__ int32_t s_tile_row[kTileRowBatch];
+
+    const SpmmArgs& a = s.a;
+    const int tid = threadIdx.x;
+    const int slot = tid / G;
+    const int member = tid % G;
+    const int64_t J = a.N;
+    const float* __restrict__ X2T = a.B;
+    const int32_t nnz = a.rowptr[a.M];
+    const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
+    if ((int64_t)blockIdx.x >= tiles) return;
+    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    // this lane's columns: (st*G + member)*4, st < S
+    bool c_ok[S];
+#pragma unroll
+    for (int st = 0; st < S; ++st) c_ok[st] = (int64_t)(st * G + member) * VEC < J;
+
+    for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
+        find_tile_rows(a, j0, my_tiles, kSddmmTile, s_tile_row);
+        const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
+        for (int64_t j = j0; j < j1; ++j) {
+            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int32_t tile_start = (int32_t)(t * kSddmmTile);
+            const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
+            const int cnt = tile_end - tile_start;
+            int32_t row_lb = s_tile_row[j - j0];
+
+            __syncthreads();  // the previous tile is consumed
+            for (int i = tid; i < cnt; i += kBlock) {
+                s_col[i] = load_stream(a.colidx + tile_start + i);
+                s_val[i] = load_stream(a.vals + tile_start + i);
+            }
+            for (int32_t base = tile_start; base < tile_end;) {
+                __syncthreads();
+                const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
+                for (int i = tid; i < w.cnt; i += kBlock)
+                    s_row[base - tile_start + i] =
+                        row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
+                row_lb += w.n_last;
+                base += w.cnt;
+            }
+            __syncthreads();
+
+            int32_t cur_row = -1;
+            Vec<VEC> x1c[S];  // the chunk of X1[cur_row] this lane owns
+#pragma unroll
+            for (int st = 0; st < S; ++st) x1c[st].zero();
+            for (int i0 = 0; i0 < EPS; i0 += U) {  // same trip count in every lane
+                int32_t row[U], col[U];
+                bool ok[U], fresh[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = (i0 / U * SLOTS + slot) * U + u;
+                    ok[u] = e < cnt;
+                    row[u] = ok[u] ? s_row[e] : (u ? row[u - 1] : cur_row);
+                    col[u] = ok[u] ? s_col[e] : 0;
+                    fresh[u] = ok[u] && row[u] != (u ? row[u - 1] : cur_row);
+                }
+                Vec<VEC> x1[U][S], x2[U][S];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+#pragma unroll
+                    for (int st = 0; st < S; ++st) {
+                        const int64_t c = (int64_t)(st * G + member) * VEC;
+                        x2[u][st].zero();
+                        x1[u][st].zero();
+                        if (ok[u] && c_ok[st]) x2[u][st] = load_vec<VEC>(X2T + (int64_t)col[u] * J + c);
+                        if (fresh[u] && c_ok[st]) x1[u][st] = load_vec<VEC>(s.X1 + (int64_t)row[u] * J + c);
+                    }
+                }
+                float acc[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    acc[u] = 0.0f;
+#pragma unroll
+                    for (int st = 0; st < S; ++st) {
+                        if (fresh[u]) x1c[st] = x1[u][st];
+                        acc[u] = dot_vec<VEC>(x1c[st], x2[u][st], acc[u]);
+                    }
+                }
+                cur_row = row[U - 1];
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] = group_tree_sum<G, 1>(acc[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = (i0 / U * SLOTS + slot) * U + u;
+                    if (member == 0 && ok[u]) s_val[e] *= acc[u];  // this group is the entry's only reader
+                }
+            }
+            __syncthreads();
+            for (int i = tid; i < cnt; i += kBlock) s.out[tile_start + i] = s_val[i];
+        }
+    }
+}
+
 namespace {
+
+template <int G, int S>
+void launch_rowcache(const SddmmArgs& s, int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    static const int per_cu = resident_per_cu(sddmm_rowcache_kernel<G, S>, 0);
+    const int grid = persistent_grid(per_cu, compute_units, nnz_hint, kSddmmTile);
+    hipLaunchKernelGGL((sddmm_rowcache_kernel<G, S>), dim3(grid), dim3(kBlock), 0, stream, s);
+}
+
+// steps of G*4 columns that cover J: 1, 2 or 4 pick the row-cache kernel, 0 = more than 4
+template <int G>
+bool try_rowcache(const SddmmArgs& s, int64_t J, int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    const int64_t steps = (J + G * 4 - 1) / (G * 4);
+    if (steps <= 1) launch_rowcache<G, 1>(s, compute_units, nnz_hint, stream);
+    else if (steps <= 2) launch_rowcache<G, 2>(s, compute_units, nnz_hint, stream);
+    else if (steps <= 4) launch_rowcache<G, 4>(s, compute_units, nnz_hint, stream);
+    else return false;
+    return true;
+}
 
 template <int G, int VEC>
 void launch_one(const SddmmArgs& s, int per_lane, int compute_units, int64_t nnz_hint, hipStream_t stream)
@@ -187,7 +323,9 @@ bool launch_vec(const SddmmArgs& s, int vec, int per_lane, int compute_units, in
 // stored entry (parallel strategy, per_lane = 0) or 1 with per_lane = entries
 // per lane (serial strategy).  vec = columns per lane and load (4, 2 or 1;
 // J % vec == 0 and matching alignment of X1 and X2T).
-hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec,
+// row_cache: let the parallel strategy keep rows of X1 in registers where the
+// shape allows it.
+hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec, bool row_cache,
                         int compute_units, int64_t nnz_hint, hipStream_t stream)
 {
     SddmmArgs s;
@@ -197,6 +335,18 @@ hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, i
     bool ok = false;
     if (per_lane > 0) {
         ok = launch_vec<1>(s, vec, per_lane, compute_units, nnz_hint, stream);
+    } else if (vec == 4 && row_cache && a.N > 0) {
+        switch (g) {
+            case 1: ok = try_rowcache<1>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 2: ok = try_rowcache<2>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 4: ok = try_rowcache<4>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 8: ok = try_rowcache<8>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 16: ok = try_rowcache<16>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 32: ok = try_rowcache<32>(s, a.N, compute_units, nnz_hint, stream); break;
+            case 64: ok = try_rowcache<64>(s, a.N, compute_units, nnz_hint, stream); break;
+            default: break;
+        }
+        if (!ok) return launch_sddmm(a, X1, out, g, per_lane, vec, false, compute_units, nnz_hint, stream);
     } else {
         switch (g) {
             case 1: ok = launch_vec<1>(s, vec, 0, compute_units, nnz_hint, stream); break;

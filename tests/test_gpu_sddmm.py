@@ -35,8 +35,16 @@ def test_every_point_matches_the_oracle(name, kw):
     ref, bnd = oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=8)
     dp = DeviceProblem(p)
     X1d = torch.from_numpy(X1).cuda()
-    for g, st in SDDMM_POINTS:
-        check(dp.run_sddmm(X1d, g, st), ref, bnd, name.endswith("_int"), f"{name} {kw} g={g} {st}")
+    try:
+        for cache in (1, 0):  # with and without rows of X1 kept in registers
+            binding.sgap_set_tuning(binding.SGAP_TUNE_SDDMM_ROW_CACHE, cache)
+            for g, st in SDDMM_POINTS:
+                if cache == 0 and st == "serial":
+                    continue  # the knob only concerns the parallel strategy
+                check(dp.run_sddmm(X1d, g, st), ref, bnd, name.endswith("_int"),
+                      f"{name} {kw} g={g} {st} row cache {cache}")
+    finally:
+        binding.sgap_set_tuning(binding.SGAP_TUNE_SDDMM_ROW_CACHE, 1)
 
 
 @pytest.mark.parametrize("name,kw", [("powerlaw", dict(scale_down=4)), ("rmat", dict(scale_down=64)),
