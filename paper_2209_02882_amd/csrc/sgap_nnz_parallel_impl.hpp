@@ -167,9 +167,9 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
     const int32_t M = (int32_t)a.M;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kParTile - 1) / kParTile;
-    if ((int64_t)blockIdx.x >= tiles) return;
-    // this workgroup's tiles: blockIdx.x + j * gridDim.x, j = 0 .. my_tiles-1
-    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const TileDeal deal(tiles);
+    const int64_t my_tiles = deal.mine;
+    if (my_tiles == 0) return;
     const int tid = threadIdx.x;
 
     if constexpr (MERGE) merge_reset(mb);  // made visible by the barriers below
@@ -199,12 +199,12 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
     };
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        find_tile_rows(a, j0, my_tiles, kParTile, s_tile_row);
+        find_tile_rows(a, deal, j0, kParTile, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
-        fetch_tile(blockIdx.x + j0 * gridDim.x, s_tile_row[0]);
+        fetch_tile(deal.tile(j0), s_tile_row[0]);
 
         for (int64_t j = j0; j < j1; ++j) {
-            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int64_t t = deal.tile(j);
             const int32_t tile_start = (int32_t)(t * kParTile);
             const int32_t tile_end = nnz - tile_start < kParTile ? nnz : tile_start + kParTile;
             int32_t row_lb = s_tile_row[j - j0];
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
                               s_win, s_tile);
                 __syncthreads();
                 // start bringing in the next tile of this batch
-                if (j + 1 < j1) fetch_tile(t + gridDim.x, s_tile_row[j + 1 - j0]);
+                if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
                 parallel_chunk<G, LC, VEC, OFF32, MERGE>(a, mb, s_tile);
             } else {
                 // long runs of rows without entries: cut the tile at row
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
                     row_lb += w.n_last;
                     base += w.cnt;
                 }
-                if (j + 1 < j1) fetch_tile(t + gridDim.x, s_tile_row[j + 1 - j0]);
+                if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
             }
         }
     }

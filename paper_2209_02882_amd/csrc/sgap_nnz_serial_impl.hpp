@@ -153,9 +153,9 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
     const int32_t M = (int32_t)a.M;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + TILE - 1) / TILE;
-    if ((int64_t)blockIdx.x >= tiles) return;
-    // this workgroup's tiles: blockIdx.x + j * gridDim.x, j = 0 .. my_tiles-1
-    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const TileDeal deal(tiles);
+    const int64_t my_tiles = deal.mine;
+    if (my_tiles == 0) return;
     const int tid = threadIdx.x;
 
     if constexpr (MERGE) merge_reset(mb);  // made visible by the barriers below
@@ -185,12 +185,12 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
     };
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        find_tile_rows(a, j0, my_tiles, TILE, s_tile_row);
+        find_tile_rows(a, deal, j0, TILE, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
-        fetch_tile(blockIdx.x + j0 * gridDim.x, s_tile_row[0]);
+        fetch_tile(deal.tile(j0), s_tile_row[0]);
 
         for (int64_t j = j0; j < j1; ++j) {
-            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int64_t t = deal.tile(j);
             const int32_t tile_start = (int32_t)(t * TILE);
             const int32_t tile_end = nnz - tile_start < TILE ? nnz : tile_start + TILE;
             int32_t row_lb = s_tile_row[j - j0];
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
                 if (tid + i * kBlock <= kWindowCap) s_win[tid + i * kBlock] = nx_win[i];
             __syncthreads();
             // start bringing in the next tile of this batch
-            if (j + 1 < j1) fetch_tile(t + gridDim.x, s_tile_row[j + 1 - j0]);
+            if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
 
             if (s_win[kWindowCap] >= tile_end) {
                 // the window covers every row of the tile: one chunk

@@ -14,8 +14,8 @@
 // Every output has exactly one writer: no atomics, no zeroing.
 //
 // The unit of work is a stored entry, so the schedule is nnz-balanced by
-// construction: tiles of 1024 entries are dealt round-robin to persistent
-// workgroups, the rows of a tile's entries come from a bisection of rowptr
+// construction: tiles of 1024 entries are dealt to persistent workgroups
+// (chunks of neighbouring tiles per die, see TileDeal), the rows of a tile's entries come from a bisection of rowptr
 // for the tile's first entry and an LDS window of rowptr for the rest (the
 // same pieces as the nnz-balanced SpMM kernels).
 #include "sgap_common.hpp"
@@ -61,14 +61,15 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
     const float* __restrict__ X2T = a.B;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
-    if ((int64_t)blockIdx.x >= tiles) return;
-    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const TileDeal deal(tiles);
+    const int64_t my_tiles = deal.mine;
+    if (my_tiles == 0) return;
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        find_tile_rows(a, j0, my_tiles, kSddmmTile, s_tile_row);
+        find_tile_rows(a, deal, j0, kSddmmTile, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
         for (int64_t j = j0; j < j1; ++j) {
-            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int64_t t = deal.tile(j);
             const int32_t tile_start = (int32_t)(t * kSddmmTile);
             const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
             const int cnt = tile_end - tile_start;
@@ -191,18 +192,19 @@ __global__ __launch_bounds__(kBlock) void sddmm_rowcache_kernel(SddmmArgs s)
     const float* __restrict__ X2T = a.B;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
-    if ((int64_t)blockIdx.x >= tiles) return;
-    const int64_t my_tiles = (tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const TileDeal deal(tiles);
+    const int64_t my_tiles = deal.mine;
+    if (my_tiles == 0) return;
     // this lane's columns: (st*G + member)*4, st < S
     bool c_ok[S];
 #pragma unroll
     for (int st = 0; st < S; ++st) c_ok[st] = (int64_t)(st * G + member) * VEC < J;
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
-        find_tile_rows(a, j0, my_tiles, kSddmmTile, s_tile_row);
+        find_tile_rows(a, deal, j0, kSddmmTile, s_tile_row);
         const int64_t j1 = j0 + kTileRowBatch < my_tiles ? j0 + kTileRowBatch : my_tiles;
         for (int64_t j = j0; j < j1; ++j) {
-            const int64_t t = blockIdx.x + j * gridDim.x;
+            const int64_t t = deal.tile(j);
             const int32_t tile_start = (int32_t)(t * kSddmmTile);
             const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
             const int cnt = tile_end - tile_start;
