@@ -16,8 +16,9 @@
 //             G = 1 and rows_per_slot = group_size.
 // Lane layout:  thread = (slot*G + member)*LC + chunk over the workgroup.
 //
-// Workgroups are persistent.  A work item is (block of consecutive rows,
-// column tile); the stored entries of a row block are contiguous in
+// A work item is (block of consecutive rows, column tile), one workgroup per
+// item (or, as a tuning option, a grid that fits the chip at once whose
+// workgroups loop over items); the stored entries of a row block are contiguous in
 // colidx/vals, so the workgroup copies them (coalesced, streaming) into LDS in
 // chunks together with the block's slice of rowptr, and its lanes then read
 // (column, value) pairs from LDS: the vector memory path carries only the

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import oracle
+from paper_2209_02882_amd import binding
 from paper_2209_02882_amd import workloads as wl
 
 from gpu_util import POINTS, TOL, DeviceProblem, sample_rows
@@ -29,3 +30,42 @@ def test_full_size_sampled_rows(name):
         got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
         bad = np.abs(got - C_ref) > TOL * BND
         assert not bad.any(), f"{name} {point}: {int(bad.sum())} sampled elements out of tolerance"
+
+
+@pytest.mark.parametrize("name", ["stencil27", "rmat"])
+def test_full_size_reduce_width_below_group_size(name):
+    # a few {<1/g row, c col>, r} points with r < g at full size
+    p = wl.make_problem(name)
+    dp = DeviceProblem(p)
+    rows = sample_rows(p)
+    C_ref, BND = oracle.spmm_csr_rows(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, rows)
+    rows_t = torch.from_numpy(rows).cuda()
+    C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
+    for g, r in [(4, 2), (8, 1), (32, 8), (64, 16)]:
+        print("  g, r", g, r, flush=True)
+        C.fill_(float("nan"))
+        dp.launch_gr(C, g, r)
+        torch.cuda.synchronize()
+        assert not torch.isnan(C).any(), f"{name} g={g} r={r}: element never written"
+        got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
+        bad = np.abs(got - C_ref) > TOL * BND
+        assert not bad.any(), f"{name} g={g} r={r}: {int(bad.sum())} sampled elements out of tolerance"
+
+
+@pytest.mark.parametrize("name", ["stencil27", "rmat", "skewed"])
+def test_full_size_sddmm_every_entry(name):
+    # the SDDMM oracle is fast enough to check every stored entry at full size
+    p = wl.make_problem(name)
+    X1 = wl.sddmm_left_operand(p)
+    ref, bnd = oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=16)
+    dp = DeviceProblem(p)
+    X1d = torch.from_numpy(X1).cuda()
+    ref_t = torch.from_numpy(ref).cuda()
+    bnd_t = torch.from_numpy(bnd).cuda()
+    for st in ("parallel", "serial"):
+        for g in binding.GROUP_SIZES:
+            print("  sddmm point", g, st, flush=True)
+            out = dp.run_sddmm(X1d, g, st)
+            assert not torch.isnan(out).any(), f"{name} sddmm g={g} {st}: entry never written"
+            bad = (out.double() - ref_t).abs() > TOL * bnd_t
+            assert not bool(bad.any()), f"{name} sddmm g={g} {st}: {int(bad.sum())} entries out of tolerance"
