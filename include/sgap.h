@@ -67,9 +67,11 @@ typedef enum {
  *     nnz-balanced schedule: lane = group_size consecutive stored entries
  *       ({<g nnz, c col>, 1}, Section 6.1).
  *
- * In the nnz-balanced schedule a row whose entries all lie inside one aligned
- * block of group_size positions is written with a plain store; any other
- * non-empty row is zeroed first and receives its partial sums by atomic adds.
+ * In the nnz-balanced schedule a row whose stored entries all lie inside one
+ * aligned block of positions (group_size positions, or a whole tile of about a
+ * thousand when the partial sums of a tile fit on chip) is written with one
+ * plain store; only a row that crosses such a block is zeroed first and
+ * receives its partial sums by atomic adds.
  */
 typedef enum { SGAP_REDUCE_PARALLEL = 0, SGAP_REDUCE_SERIAL = 1 } sgap_strategy;
 
@@ -133,7 +135,8 @@ int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N,
  * and split its stored entries; every `reduce_size` = r neighbouring lanes of
  * them (power of two, 1 <= r <= g) tree-sum their partial sums, and the g/r
  * sub-group sums of a row are merged into C with atomic adds (r = 1: every
- * lane adds its own sum, the "Atomics" strategy of Section 5.1).  r = g is
+ * lane adds its own sum: the group is parallelised with the "Atomics" output
+ * strategy alone, as in the schedule printed in Section 6.2).  r = g is
  * sgap_spmm_csr_ex with the parallel strategy and the row-split schedule:
  * plain stores, no atomics.  For r < g the library zeroes C first, and the
  * order of the atomic adds, hence the fp32 rounding, varies between runs.
