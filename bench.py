@@ -248,7 +248,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
-                 "(the path shards by row blocks without any exchange, see DESIGN.md)")
+                 "(the path would shard by row blocks of A and C with B replicated, no exchange step)")
 
     if a.op == "sddmm":
         return main_sddmm(a)

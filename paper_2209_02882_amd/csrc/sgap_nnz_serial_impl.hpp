@@ -98,7 +98,7 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                             const int32_t first_in_chunk = row_begin > base ? row_begin : base;
                             const int32_t slot =
                                 row_begin < base ? mb.nslots - 1 : (row_begin - tile_start) >> a.log2_group;
-                            merge_add<VEC>(mb, slot, chunk * VEC, acc, chunk == 0 && run_begin == first_in_chunk, row,
+                            merge_add<VEC, true>(mb, slot, chunk * VEC, acc, chunk == 0 && run_begin == first_in_chunk, row,
                                            row_begin < base || row_end > end);
                         }
                     } else {
