@@ -37,8 +37,12 @@ NnzPlan plan_nnz_serial(int group, int lc, int vec, int64_t nnz_hint, int comput
         }
         p.tile = best_tile;
     }
-    const int nslots = p.tile / group + 1;
-    p.merge = nslots * (lc * vec * 4 + 8) <= kMergeLdsBudget;
+    auto fits = [&](int tile) { return (tile / group + 1) * (lc * vec * 4 + 8) <= kMergeLdsBudget; };
+    // merging a tile's partial sums on chip is worth a smaller tile: the
+    // alternative is a global atomic add per partial sum
+    if (forced_tile == 0 && vec == 4)
+        while (!fits(p.tile) && p.tile > 256 && p.tile / 2 >= group) p.tile /= 2;
+    p.merge = fits(p.tile);
     int lg = 0;
     while ((1 << lg) < (p.merge ? p.tile : group)) ++lg;
     p.merge_log2 = lg;
