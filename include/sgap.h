@@ -18,6 +18,10 @@
  *     after the call returns and allocates no device memory.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and the call returns without waiting.
+ *   - A call only enqueues kernels (no allocation, no host synchronisation, no
+ *     memset nodes), so it may be recorded into a HIP graph; the first call
+ *     that uses a kernel instance asks the runtime for its occupancy and
+ *     should be made once outside a capture.
  *   - Return value: an sgap_status.  On anything but SGAP_OK nothing was
  *     launched and C is untouched; sgap_last_error() gives detail.
  *   - Preconditions that are NOT checked on the device: rowptr[0] == 0,

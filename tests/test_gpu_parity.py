@@ -404,3 +404,32 @@ def test_wide_matrix_offsets_need_64_bits():
                                  binding.SCHEDULES[point[2]])
         torch.cuda.synchronize()
         assert_close(C, C_ref, BND, exact=True, what=f"64-bit offsets {ids(point)}")
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # after one eager call per point (the first call of a kernel instance asks
+    # the runtime for its occupancy), the library only launches kernels on the
+    # caller's stream: no allocation, no synchronisation, no memset nodes
+    p = wl.make_problem("uniform10")
+    rng = np.random.default_rng(9)
+    p.vals = wl.fill_values(rng, p.nnz, True)
+    p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    points = [(8, "parallel", "row_split"), (16, "serial", "nnz_balanced"), (4, "parallel", "nnz_balanced")]
+    outs = [dp.new_output() for _ in points]
+    for C, pt in zip(outs, points):
+        dp.launch(C, *pt)  # eager warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for C, pt in zip(outs, points):
+            dp.launch(C, *pt, stream=torch.cuda.current_stream())
+    for replay in range(3):
+        for C in outs:
+            C.fill_(float("nan"))  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for C, pt in zip(outs, points):
+            assert_close(C, C_ref, BND, exact=True, what=f"graph replay {replay} {ids(pt)}")
