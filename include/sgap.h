@@ -292,6 +292,23 @@ int sgap_debug_group_partial_reduce(const float* in, float* out, int group_size,
 int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out,
                                 int group_size, int lanes_per_row, void* stream);
 
+/*
+ * Host-side pieces of the nnz-balanced schedule, exported for tests; no GPU
+ * is touched.
+ *   sgap_debug_tile_deal: which tiles of stored entries workgroup `block` of a
+ *     persistent grid of `grid` workgroups takes when the matrix has `tiles`
+ *     tiles (chunks of neighbouring tiles per die).  Writes up to `capacity`
+ *     tile numbers, ascending, into out_tiles (host) and returns how many
+ *     tiles the workgroup takes, or -1 on bad arguments.
+ *   sgap_debug_plan_nnz_serial: tile size (stored entries) and whether a
+ *     tile's partial sums are merged on chip, for the serial strategy with
+ *     lanes_per_row chunk lanes of cols_per_lane columns each on a chip of
+ *     compute_units; forced_tile as SGAP_TUNE_NNZ_TILE.  Host pointers.
+ */
+int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_tiles, int64_t capacity);
+int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
+                               int compute_units, int forced_tile, int* tile, int* merge_on_chip);
+
 /* Plain device-to-device fp32 copy kernel (n elements).  Used to calibrate
  * hardware traffic counters and to report a streaming-bandwidth reference. */
 int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream);

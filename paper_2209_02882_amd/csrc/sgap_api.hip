@@ -9,6 +9,7 @@
 
 #include "sgap_common.hpp"
 #include "sgap_lane_ops.hpp"
+#include "sgap_tile_deal.hpp"
 
 namespace sgap {
 
@@ -478,6 +479,31 @@ int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out
     hipError_t err = sgap::launch_debug_group_seg_reduce(in, span, out, group_size, lanes_per_row,
                                                          reinterpret_cast<hipStream_t>(stream));
     if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_tiles, int64_t capacity)
+{
+    if (tiles < 0 || grid < 1 || block < 0 || block >= grid || capacity < 0 || (capacity > 0 && !out_tiles)) {
+        fail(SGAP_ERR_INVALID_ARG, "bad tile deal arguments");
+        return -1;
+    }
+    const sgap::TileDeal deal(tiles, (uint32_t)block, (uint32_t)grid);
+    for (int64_t j = 0; j < deal.mine && j < capacity; ++j) out_tiles[j] = deal.tile(j);
+    return deal.mine;
+}
+
+int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
+                               int compute_units_, int forced_tile, int* tile, int* merge_on_chip)
+{
+    if (!is_pow2_group(group_size) || !is_pow2_group(lanes_per_row) ||
+        (cols_per_lane != 1 && cols_per_lane != 2 && cols_per_lane != 4) || compute_units_ < 1 || !tile ||
+        !merge_on_chip)
+        return fail(SGAP_ERR_INVALID_ARG, "bad plan arguments");
+    const sgap::NnzPlan p =
+        sgap::plan_nnz_serial(group_size, lanes_per_row, cols_per_lane, nnz_hint, compute_units_, forced_tile);
+    *tile = p.tile;
+    *merge_on_chip = p.merge ? 1 : 0;
     return SGAP_OK;
 }
 

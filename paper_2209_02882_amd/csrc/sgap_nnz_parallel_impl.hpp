@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
     const int32_t M = (int32_t)a.M;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kParTile - 1) / kParTile;
-    const TileDeal deal(tiles);
+    const TileDeal deal(tiles, blockIdx.x, gridDim.x);
     const int64_t my_tiles = deal.mine;
     if (my_tiles == 0) return;
     const int tid = threadIdx.x;

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
     const float* __restrict__ X2T = a.B;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
-    const TileDeal deal(tiles);
+    const TileDeal deal(tiles, blockIdx.x, gridDim.x);
     const int64_t my_tiles = deal.mine;
     if (my_tiles == 0) return;
 
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_rowcache_kernel(SddmmArgs s)
     const float* __restrict__ X2T = a.B;
     const int32_t nnz = a.rowptr[a.M];
     const int64_t tiles = ((int64_t)nnz + kSddmmTile - 1) / kSddmmTile;
-    const TileDeal deal(tiles);
+    const TileDeal deal(tiles, blockIdx.x, gridDim.x);
     const int64_t my_tiles = deal.mine;
     if (my_tiles == 0) return;
     // this lane's columns: (st*G + member)*4, st < S

@@ -127,3 +127,58 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(4)
     with pytest.raises(TypeError):
         binding.sgap_copy_f32(t, t)
+
+
+def tile_deal(lib, tiles, grid, block):
+    cap = tiles + 1
+    buf = (ctypes.c_int64 * cap)()
+    n = lib.sgap_debug_tile_deal(tiles, grid, block, buf, cap)
+    assert 0 <= n <= tiles
+    return list(buf[:n])
+
+
+@pytest.mark.parametrize("tiles,grid", [(0, 1), (1, 1), (7, 7), (8, 8), (9, 8), (100, 16), (1000, 1024), (1029, 1024),
+                                        (4117, 1024), (48754, 1024), (25844, 1280), (777, 40), (5000, 1000), (333, 24)])
+def test_every_tile_goes_to_exactly_one_workgroup(tiles, grid):
+    lib = binding.load()
+    seen = []
+    per_die = {}
+    for b in range(grid):
+        mine = tile_deal(lib, tiles, grid, b)
+        assert mine == sorted(mine), "a workgroup walks its tiles in ascending order"
+        seen += mine
+        per_die.setdefault(b % 8 if grid >= 8 and grid % 8 == 0 else 0, []).extend(mine)
+    assert sorted(seen) == list(range(tiles))
+    if tiles >= 8 * 64 and grid % 8 == 0:
+        # every die gets an even share, in runs of neighbouring tiles
+        sizes = [len(v) for v in per_die.values()]
+        assert max(sizes) - min(sizes) <= max(1, tiles // 64)
+        t = sorted(per_die[0])
+        runs = 1 + sum(1 for x, y in zip(t, t[1:]) if y != x + 1)
+        # chunks of about tiles/128 neighbouring tiles, at most one round of the die's workgroups
+        chunk = max(1, min(tiles // 128, grid // 8))
+        assert runs <= -(-tiles // chunk) // 8 + 1
+    assert lib.sgap_debug_tile_deal(10, 4, 4, None, 0) == -1
+
+
+def test_serial_plan_keeps_partial_sums_on_chip_and_fills_the_chip():
+    lib = binding.load()
+
+    def plan(g, lc, vec, nnz, cus=256, forced=0):
+        tile, merge = ctypes.c_int(), ctypes.c_int()
+        assert lib.sgap_debug_plan_nnz_serial(g, lc, vec, nnz, cus, forced, ctypes.byref(tile), ctypes.byref(merge)) == 0
+        return tile.value, bool(merge.value)
+
+    # large matrices: 1024 or 2048 entries, shrunk until the slots fit 34 KB
+    assert plan(32, 8, 4, 50_000_000) == (1024, True)
+    assert plan(64, 1, 4, 50_000_000) == (2048, True)
+    assert plan(8, 32, 4, 26_000_000) == (512, True)      # 128 columns: 65 slots of 520 bytes
+    assert plan(2, 32, 4, 26_000_000) == (256, False)     # does not fit even at 256: global atomics
+    # small matrices: smaller tiles so that the chip's ~1024 resident workgroups all get work
+    assert plan(16, 8, 4, 10_240)[0] == 256
+    assert plan(16, 16, 4, 1_053_925)[0] in (256, 512)
+    # unknown nnz, narrow loads or a forced size keep the base choice / the forced one
+    assert plan(16, 8, 4, -1)[0] == 1024
+    assert plan(16, 8, 2, 10_240)[0] == 1024
+    assert plan(16, 8, 4, 10_240, forced=2048)[0] == 2048
+    assert lib.sgap_debug_plan_nnz_serial(3, 8, 4, 0, 256, 0, None, None) == binding.SGAP_ERR_INVALID_ARG
