@@ -41,6 +41,32 @@ __device__ __forceinline__ float dot_vec(const Vec<VEC>& x, const Vec<VEC>& y, f
     return acc;
 }
 
+// Copy the tile's columns and values into LDS and look up the row of every
+// entry through the rowptr window (cut at row boundaries where long runs of
+// empty rows overflow it).  row_lb = a row at or before the tile's first
+// entry.  Block-uniform; the LDS arrays are ready on return.
+__device__ __forceinline__ void stage_tile(const SpmmArgs& a, int32_t tile_start, int32_t tile_end, int32_t row_lb,
+                                           int32_t* __restrict__ s_col, float* __restrict__ s_val,
+                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_win)
+{
+    const int tid = threadIdx.x;
+    const int cnt = tile_end - tile_start;
+    __syncthreads();  // the previous tile is consumed
+    for (int i = tid; i < cnt; i += kBlock) {
+        s_col[i] = load_stream(a.colidx + tile_start + i);
+        s_val[i] = load_stream(a.vals + tile_start + i);
+    }
+    for (int32_t base = tile_start; base < tile_end;) {
+        __syncthreads();
+        const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
+        for (int i = tid; i < w.cnt; i += kBlock)
+            s_row[base - tile_start + i] = row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
+        row_lb += w.n_last;
+        base += w.cnt;
+    }
+    __syncthreads();
+}
+
 // per_lane = 0: parallel strategy, G lanes per entry.  per_lane > 0 (G = 1):
 // serial strategy, per_lane consecutive entries per lane.
 template <int G, int VEC>
@@ -73,25 +99,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
             const int32_t tile_start = (int32_t)(t * kSddmmTile);
             const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
             const int cnt = tile_end - tile_start;
-            int32_t row_lb = s_tile_row[j - j0];
+            const int32_t row_lb = s_tile_row[j - j0];
 
-            __syncthreads();  // the previous tile is consumed
-            for (int i = tid; i < cnt; i += kBlock) {
-                s_col[i] = load_stream(a.colidx + tile_start + i);
-                s_val[i] = load_stream(a.vals + tile_start + i);
-            }
-            // the row of every entry, through the rowptr window (cut at row
-            // boundaries where long runs of empty rows overflow it)
-            for (int32_t base = tile_start; base < tile_end;) {
-                __syncthreads();
-                const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
-                for (int i = tid; i < w.cnt; i += kBlock)
-                    s_row[base - tile_start + i] =
-                        row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
-                row_lb += w.n_last;
-                base += w.cnt;
-            }
-            __syncthreads();
+            stage_tile(a, tile_start, tile_end, row_lb, s_col, s_val, s_row, s_win);
 
             if (per_lane == 0) {
                 // U entries per group at a time, so that 2*U rows are in flight
@@ -208,23 +218,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_rowcache_kernel(SddmmArgs s)
             const int32_t tile_start = (int32_t)(t * kSddmmTile);
             const int32_t tile_end = nnz - tile_start < kSddmmTile ? nnz : tile_start + kSddmmTile;
             const int cnt = tile_end - tile_start;
-            int32_t row_lb = s_tile_row[j - j0];
+            const int32_t row_lb = s_tile_row[j - j0];
 
-            __syncthreads();  // the previous tile is consumed
-            for (int i = tid; i < cnt; i += kBlock) {
-                s_col[i] = load_stream(a.colidx + tile_start + i);
-                s_val[i] = load_stream(a.vals + tile_start + i);
-            }
-            for (int32_t base = tile_start; base < tile_end;) {
-                __syncthreads();
-                const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
-                for (int i = tid; i < w.cnt; i += kBlock)
-                    s_row[base - tile_start + i] =
-                        row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
-                row_lb += w.n_last;
-                base += w.cnt;
-            }
-            __syncthreads();
+            stage_tile(a, tile_start, tile_end, row_lb, s_col, s_val, s_row, s_win);
 
             int32_t cur_row = -1;
             Vec<VEC> x1c[S];  // the chunk of X1[cur_row] this lane owns
