@@ -27,18 +27,18 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # scaled by the same counters on the library's plain copy kernel; keyed by
 # (workload, group, strategy, schedule).  See profiles/ for the runs.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("stencil27", 1, "parallel", "row_split"): 2_273_812_896,   # profiles/row_split_kernel_stencil27.md
-    ("stencil27", 1, "serial", "row_split"): 2_260_592_782,     # profiles/row_split_kernel_stencil27_serial.md
-    ("rmat", 16, "serial", "nnz_balanced"): 4_399_354_198,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
-    ("skewed", 64, "serial", "nnz_balanced"): 59_904_578_275,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
-    ("powerlaw", 16, "serial", "nnz_balanced"): 242_835_967,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
+    ("stencil27", 1, "parallel", "row_split"): 2_287_184_383,   # profiles/row_split_kernel_stencil27.md
+    ("stencil27", 1, "serial", "row_split"): 2_260_465_487,     # profiles/row_split_kernel_stencil27_serial.md
+    ("rmat", 16, "serial", "nnz_balanced"): 4_398_701_021,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
+    ("skewed", 64, "serial", "nnz_balanced"): 59_904_989_739,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
+    ("powerlaw", 16, "serial", "nnz_balanced"): 242_820_253,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
 }
 
 
 # the same for --op sddmm, keyed by (workload, group, strategy)
 MEASURED_SDDMM_TRAFFIC_BYTES: dict = {
-    ("stencil27", 8, "parallel"): 4_617_012_411,   # profiles/sddmm_rowcache_kernel_stencil27.md
-    ("rmat", 8, "parallel"): 4_639_674_817,        # profiles/sddmm_rowcache_kernel_rmat.md
+    ("stencil27", 8, "parallel"): 4_622_814_612,   # profiles/sddmm_rowcache_kernel_stencil27.md
+    ("rmat", 8, "parallel"): 4_640_438_673,        # profiles/sddmm_rowcache_kernel_rmat.md
 }
 
 
