@@ -42,16 +42,18 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
 
         const int64_t row_first = row_block * rows_per_block;
         const int64_t row_last = row_first + rows_per_block < a.M ? row_first + rows_per_block : a.M;
-        // this slot's rows: my_first, my_first + row_step, ... below my_last
-        const int64_t row_step = interleave ? SLOTS : 1;
-        int64_t my_first = row_first + (interleave ? (int64_t)slot : (int64_t)slot * rows_per_slot);
-        int64_t my_last = interleave ? row_last : my_first + rows_per_slot;
-        if (my_first > row_last) my_first = row_last;
-        if (my_last > row_last) my_last = row_last;
+        // this slot's rows, counted from row_first: my_first, my_first + row_step, ... below my_last
+        // (32-bit: a row block has at most SLOTS * rows_per_slot rows)
+        const int32_t block_rows = (int32_t)(row_last - row_first);
+        const int32_t row_step = interleave ? SLOTS : 1;
+        int32_t my_first = interleave ? slot : slot * rows_per_slot;
+        int32_t my_last = interleave ? block_rows : my_first + rows_per_slot;
+        if (my_first > block_rows) my_first = block_rows;
+        if (my_last > block_rows) my_last = block_rows;
 
         __syncthreads();  // everyone is done with the previous item's LDS contents
         if (rp_in_lds) {
-            for (int i = threadIdx.x; i <= (int)(row_last - row_first); i += kBlock)
+            for (int i = threadIdx.x; i <= block_rows; i += kBlock)
                 s_rp[i] = a.rowptr[row_first + i];
             __syncthreads();
         }
@@ -62,11 +64,11 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
             (int64_t)(col_tile + 1) * ts.tile_cols < N ? (int64_t)(col_tile + 1) * ts.tile_cols : N;
         // a tile may be wider than one pass of the LC chunk lanes
         for (int64_t k0 = (int64_t)col_tile * ts.tile_cols; k0 < k_tile_end; k0 += (int64_t)LC * VEC) {
-            const int64_t k = k0 + (int64_t)chunk * VEC;
+            const int32_t k = (int32_t)k0 + chunk * VEC;  // N < 2^31
             const bool k_ok = k < k_tile_end;
             const GlobalRows<VEC, OFF32> Brow(a.B, N, k);
 
-            int64_t row = my_first;
+            int32_t row = my_first;
             Vec<VEC> acc;
             acc.zero();
             for (uint32_t base = nz_first;; base += kStageCap) {  // runs at least once: empty rows get stored
@@ -78,11 +80,11 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                 while (row < my_last) {
                     uint32_t p_begin, p_end;
                     if (rp_in_lds) {
-                        p_begin = (uint32_t)s_rp[row - row_first];
-                        p_end = (uint32_t)s_rp[row - row_first + 1];
+                        p_begin = (uint32_t)s_rp[row];
+                        p_end = (uint32_t)s_rp[row + 1];
                     } else {
-                        p_begin = (uint32_t)a.rowptr[row];
-                        p_end = (uint32_t)a.rowptr[row + 1];
+                        p_begin = (uint32_t)a.rowptr[row_first + row];
+                        p_end = (uint32_t)a.rowptr[row_first + row + 1];
                     }
                     const uint32_t lo = p_begin > base ? p_begin : base;
                     const uint32_t hi = p_end < base + cnt ? p_end : base + cnt;
@@ -100,11 +102,11 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                             acc.v[i] = group_partial_sum<G, LC>(acc.v[i], reduce_members * LC);
                         // a sub-group whose first member has no entry of the row holds +0
                         if ((member & (reduce_members - 1)) == 0 && k_ok && (uint32_t)member < p_end - p_begin)
-                            atomic_add_vec<VEC>(a.C + row * N + k, acc);
+                            atomic_add_vec<VEC>(a.C + (row_first + row) * N + k, acc);
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
-                        if (member == 0 && k_ok) store_vec_stream<VEC>(a.C + row * N + k, acc);
+                        if (member == 0 && k_ok) store_vec_stream<VEC>(a.C + (row_first + row) * N + k, acc);
                     }
                     acc.zero();
                     row += row_step;
