@@ -43,5 +43,25 @@ def build_library(jobs: int = 8) -> str:
     return LIB
 
 
+MICROBENCH = os.path.join(HERE, "microbench")
+
+
+def build_microbenchmarks() -> list[str]:
+    """Compile the standalone microbenchmarks (microbench/*.hip -> microbench/bin/)."""
+    out_dir = os.path.join(MICROBENCH, "bin")
+    os.makedirs(out_dir, exist_ok=True)
+    built = []
+    for src in sorted(f for f in os.listdir(MICROBENCH) if f.endswith(".hip")):
+        exe = os.path.join(out_dir, src[:-4])
+        cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-Wno-unused-command-line-argument", os.path.join(MICROBENCH, src), "-o", exe]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr}")
+        built.append(exe)
+    return built
+
+
 if __name__ == "__main__":
     print(build_library())
+    print("\n".join(build_microbenchmarks()))
