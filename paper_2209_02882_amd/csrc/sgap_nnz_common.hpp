@@ -248,11 +248,12 @@ inline int resident_per_cu(K kernel, int smem)
 inline int persistent_grid(int per_cu, int compute_units, int64_t nnz_hint, int tile)
 {
     int64_t grid = (int64_t)per_cu * compute_units;
-    if (nnz_hint >= 0) {
-        const int64_t tiles = (nnz_hint + tile - 1) / tile;
-        if (tiles < grid) grid = tiles > 0 ? tiles : 1;
-    }
     if (grid >= 8) grid -= grid % 8;  // whole rounds of the 8 dies, see TileDeal
+    if (nnz_hint >= 0) {
+        // a matrix with no more tiles than that gets one workgroup per tile
+        const int64_t tiles = (nnz_hint + tile - 1) / tile;
+        if (tiles <= grid) grid = tiles > 0 ? tiles : 1;
+    }
     return (int)grid;
 }
 

@@ -22,8 +22,6 @@
 
 namespace sgap {
 
-constexpr int kDepth = 8;          // gathered rows of B in flight per lane
-
 // Multiply out the chunk [base, end) of the tile staged in s_A (slot s holds
 // position tile_start + s), whose rows are s_win[w.n_first .. w.n_last + 1]
 // relative to row_lb.  MERGE selects tile mode of the merge rule.
@@ -32,6 +30,14 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                                              const int32_t* __restrict__ s_win, const RowWindow& w, int32_t row_lb,
                                              int32_t tile_start, int32_t base, int32_t end)
 {
+    constexpr int kDepth = 8;  // gathered rows of B in flight per lane
+    // How partial sums are added into the LDS slots.  With many chunk lanes per
+    // entry a wavefront holds few entry lanes, two or three of which meet on a
+    // row's slot: the compare-and-swap loop wins.  With few chunk lanes a
+    // wavefront holds up to 64 entry lanes, whole rows of which meet on one
+    // slot, and the loop would retry once per lane: the hardware atomic wins
+    // (rmat at N=4, one entry per lane: 1.6 ms against 23 ms).
+    constexpr bool kCasMerge = LC >= 8;
     constexpr int ENTRY_LANES = kBlock / LC;
     const int entry_lane = threadIdx.x / LC;
     const int chunk = threadIdx.x % LC;
@@ -98,7 +104,7 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                             const int32_t first_in_chunk = row_begin > base ? row_begin : base;
                             const int32_t slot =
                                 row_begin < base ? mb.nslots - 1 : (row_begin - tile_start) >> a.log2_group;
-                            merge_add<VEC, true>(mb, slot, chunk * VEC, acc, chunk == 0 && run_begin == first_in_chunk, row,
+                            merge_add<VEC, kCasMerge>(mb, slot, chunk * VEC, acc, chunk == 0 && run_begin == first_in_chunk, row,
                                            row_begin < base || row_end > end);
                         }
                     } else {

@@ -20,8 +20,8 @@ namespace sgap {
 // neighbouring rows of A share is fetched into one L2, not into all eight,
 // while every die still receives an even sample of the whole matrix (stretches
 // of short or empty rows cost several times more per entry than long rows).
-// With fewer than 8 workgroups, or a grid that is no multiple of 8, plain
-// round-robin over the workgroups is used.
+// With fewer than 8 workgroups, a grid that is no multiple of 8, or no more
+// tiles than workgroups, plain round-robin over the workgroups is used.
 struct TileDeal {
     int64_t tiles;   // tiles of the matrix
     int32_t dies;    // 8 or 1
@@ -34,7 +34,8 @@ struct TileDeal {
     // block = this workgroup's number in a grid of `grid` workgroups
     SGAP_HOST_DEVICE TileDeal(int64_t tiles_, uint32_t block, uint32_t grid) : tiles(tiles_)
     {
-        dies = (grid >= 8 && grid % 8 == 0) ? 8 : 1;
+        // (a grid with a workgroup per tile just takes tile = workgroup)
+        dies = (grid >= 8 && grid % 8 == 0 && tiles > grid) ? 8 : 1;
         die = (int32_t)(block % dies);
         wg = (int32_t)(block / dies);
         wgs = (int32_t)(grid / dies);

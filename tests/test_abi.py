@@ -143,13 +143,16 @@ def test_every_tile_goes_to_exactly_one_workgroup(tiles, grid):
     lib = binding.load()
     seen = []
     per_die = {}
+    by_die = grid >= 8 and grid % 8 == 0 and tiles > grid  # else plain round-robin
     for b in range(grid):
         mine = tile_deal(lib, tiles, grid, b)
         assert mine == sorted(mine), "a workgroup walks its tiles in ascending order"
         seen += mine
-        per_die.setdefault(b % 8 if grid >= 8 and grid % 8 == 0 else 0, []).extend(mine)
+        per_die.setdefault(b % 8 if by_die else 0, []).extend(mine)
     assert sorted(seen) == list(range(tiles))
-    if tiles >= 8 * 64 and grid % 8 == 0:
+    if not by_die:
+        assert all(tile_deal(lib, tiles, grid, b) == list(range(b, tiles, grid)) for b in range(grid))
+    if tiles >= 8 * 64 and by_die:
         # every die gets an even share, in runs of neighbouring tiles
         sizes = [len(v) for v in per_die.values()]
         assert max(sizes) - min(sizes) <= max(1, tiles // 64)
