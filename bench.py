@@ -22,6 +22,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate
+# Rate at which 256 compute units deliver gathered dwordx4 operands that hit in
+# L1, measured with paper_2209_02882_amd/microbench/gather_bandwidth.hip
+# (profiles/microbenchmarks.md): 55-60 bytes per clock per compute unit.
+L1_GATHER_TBS = 36.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by the same counters on the library's plain copy kernel; keyed by
@@ -58,6 +63,37 @@ def time_point(dp, torch, binding, C, point, iters):
         binding.sgap_spmm_csr_ex(*args)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / iters
+
+
+def launch_stats(torch, launch, n, flush=None):
+    """Per-launch durations in ms over n launches, timed with events on the
+    stream the launches go to (torch's current stream, which is the stream the
+    library is handed).  With `flush` (a tensor larger than every cache of the
+    chip) the caches are overwritten before each launch."""
+    evs = []
+    for _ in range(n):
+        if flush is not None:
+            flush.add_(1.0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        launch()
+        e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    return {"median": ms[len(ms) // 2], "min": ms[0], "launches": n}
+
+
+def ceilings(p):
+    """The three ceilings of a gather-reduce SpMM, as times for one launch: HBM
+    at its published rate over the minimal bytes, the vector memory path
+    delivering one operand per multiply-add (nnz*N*4 bytes) at the measured
+    L1-hit gather rate, and the fp32 vector units."""
+    return {
+        "hbm_minimal_bytes_ms": p.minimal_bytes() / (HBM_PEAK_GBS * 1e9) * 1e3,
+        "gather_l1_ms": p.nnz * p.N * 4 / (L1_GATHER_TBS * 1e12) * 1e3,
+        "fp32_vector_ms": p.flops() / (FP32_VECTOR_PEAK_TFLOPS * 1e12) * 1e3,
+    }
 
 
 def cpu_baseline(p):
@@ -216,7 +252,7 @@ def main_sddmm(a):
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st)),
+            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st)) if a.ncols is None else None,
             "kernel_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },
@@ -322,6 +358,13 @@ def main():
 
     copy_gbs = copy_reference(torch, binding)
 
+    # per-launch figures outside the timed region: median and minimum of 25
+    # launches, warm and with every cache overwritten before each launch
+    warm = launch_stats(torch, lambda: binding.sgap_spmm_csr_ex(*args), 25)
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")  # 1 GiB
+    cold = launch_stats(torch, lambda: binding.sgap_spmm_csr_ex(*args), 25, flush=flush)
+    del flush
+
     achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
     out = {
         "metric": "SpMM effective GFLOP/s (2*nnz*N/t), fp32, best (group_size, strategy, schedule) point",
@@ -341,13 +384,16 @@ def main():
         "hbm_gbs_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "copy_kernel_gbs": copy_gbs,
+        "launch_ms_warm": warm,
+        "launch_ms_caches_flushed": cold,
+        "ceilings": ceilings(p),
         "roofline": {
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc)) if a.ncols is None else None,
             "kernel_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },
