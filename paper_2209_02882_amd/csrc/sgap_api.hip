@@ -164,7 +164,7 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     if (M == 0 || N == 0) return SGAP_OK;
     if (!rowptr || !C) return fail(SGAP_ERR_INVALID_ARG, "rowptr and C must not be null");
     if (K > 0 && !B) return fail(SGAP_ERR_INVALID_ARG, "B must not be null when K > 0");
-    if (nnz_hint != 0 && K > 0 && (!colidx || !vals) && nnz_hint > 0)
+    if (nnz_hint > 0 && (!colidx || !vals))
         return fail(SGAP_ERR_INVALID_ARG, "colidx and vals must not be null when A has entries");
 
     // columns per lane (coarsening c): widest vector the shape and alignment allow

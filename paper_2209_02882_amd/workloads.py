@@ -30,6 +30,9 @@ __all__ = [
     "skewed_rows",
     "fill_values",
     "dense_operand",
+    "Tensor3Problem",
+    "make_tensor3",
+    "TENSOR_WORKLOADS",
 ]
 
 
@@ -297,3 +300,93 @@ def sddmm_left_operand(p: SpmmProblem, integer: bool | None = None) -> np.ndarra
 def sddmm_minimal_bytes(p: SpmmProblem) -> int:
     """colidx, vals read once, out written once, rowptr, X1 and X2T read once."""
     return p.nnz * 12 + (p.M + 1) * 4 + p.M * p.N * 4 + p.K * p.N * 4
+
+
+# --------------------------------------------------------------------------
+# third-order tensors (MTTKRP, TTM)
+# --------------------------------------------------------------------------
+
+@dataclass
+class Tensor3Problem:
+    """A third-order sparse tensor A[I, K, L] as compressed sparse fibers plus
+    the dense operands of MTTKRP and TTM (inputs only).
+
+    Slice i (first index, dense) owns the fibers fptr[i] .. fptr[i+1]-1; fiber
+    f has second index fidx[f] and owns the entries eptr[f] .. eptr[f+1]-1;
+    entry p has third index eidx[p] and value vals[p].  Second indices are
+    sorted and distinct inside a slice, third indices inside a fiber; no fiber
+    is empty, slices may be.  X1 is [K, J] and X2 is [L, J] (MTTKRP:
+    Y[i,j] = sum A[i,k,l] X1[k,j] X2[l,j]); for TTM along the third index the
+    dense operand is X2 (Y[i,k,:] = sum_l A[i,k,l] X2[l,:]).
+    """
+
+    name: str
+    I: int
+    K: int
+    L: int
+    J: int
+    fptr: np.ndarray  # int32 [I+1]
+    fidx: np.ndarray  # int32 [F]
+    eptr: np.ndarray  # int32 [F+1]
+    eidx: np.ndarray  # int32 [E]
+    vals: np.ndarray  # float32 [E]
+    X1: np.ndarray  # float32 [K, J]
+    X2: np.ndarray  # float32 [L, J]
+
+    @property
+    def fibers(self) -> int:
+        return int(self.fptr[-1])
+
+    @property
+    def nnz(self) -> int:
+        return int(self.eptr[-1])
+
+    def mttkrp_minimal_bytes(self) -> int:
+        """entries, fibers and slice pointers read once, both factor matrices read once, Y written once."""
+        return (self.nnz * 8 + self.fibers * 8 + 4 + (self.I + 1) * 4
+                + (self.K + self.L) * self.J * 4 + self.I * self.J * 4)
+
+    def mttkrp_flops(self) -> int:
+        """one multiply-add per entry and column, one more per fiber and column"""
+        return 2 * self.J * (self.nnz + self.fibers)
+
+    def stats(self) -> dict:
+        fl = np.diff(self.fptr.astype(np.int64))
+        el = np.diff(self.eptr.astype(np.int64))
+        return {
+            "I": self.I, "K": self.K, "L": self.L, "J": self.J, "fibers": self.fibers, "nnz": self.nnz,
+            "max_fibers_per_slice": int(fl.max()) if fl.size else 0,
+            "empty_slices": int((fl == 0).sum()),
+            "max_entries_per_fiber": int(el.max()) if el.size else 0,
+        }
+
+
+# name -> (seed, I, K, L, J, mean fibers per slice, longest fiber)
+TENSOR_WORKLOADS = {
+    "tensor3_small": (2001, 512, 256, 320, 32, 4.0, 12),
+    "tensor3_small_int": (2001, 512, 256, 320, 32, 4.0, 12),
+    "tensor3": (2002, 262_144, 65_536, 65_536, 32, 8.0, 16),
+}
+
+
+def make_tensor3(name: str, J: int | None = None) -> Tensor3Problem:
+    """Seeded random tensor: the number of fibers of a slice is geometric with
+    the given mean, minus one with probability 1/8 (so some slices are empty and
+    a few are many times longer than the mean); a fiber holds 1 .. longest entries,
+    uniformly; second and third indices are uniform distinct subsets."""
+    if name not in TENSOR_WORKLOADS:
+        raise KeyError(f"unknown tensor workload {name!r}; have {sorted(TENSOR_WORKLOADS)}")
+    seed, I, K, L, defJ, mean_fibers, longest = TENSOR_WORKLOADS[name]
+    J = defJ if J is None else int(J)
+    integer = name.endswith("_int")
+    rng = np.random.Generator(np.random.PCG64(seed))
+    fibers = rng.geometric(1.0 / mean_fibers, size=I).astype(np.int64)
+    fibers -= rng.random(I) < 0.125
+    fibers = np.minimum(fibers, K)
+    fptr, fidx = csr_from_lengths(rng, fibers, K)
+    entries = rng.integers(1, longest + 1, size=int(fptr[-1])).astype(np.int64)
+    eptr, eidx = csr_from_lengths(rng, entries, L)
+    vals = fill_values(rng, int(eptr[-1]), integer)
+    X1 = dense_operand(seed + 100, K, J, integer)
+    X2 = dense_operand(seed + 200, L, J, integer)
+    return Tensor3Problem(name, I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2)
