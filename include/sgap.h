@@ -182,6 +182,71 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J,
                    int group_size, int strategy, int64_t nnz_hint, void* stream);
 
 /*
+ * Tensor-times-matrix product along the last index of a third-order sparse
+ * tensor, the TTM form of the paper's Section 2.1 (second form under Eq. 1):
+ *   Y[i, j, l] = sum_k A[i, j, k] * X1[k, l].
+ * A is stored as compressed sparse fibers in the index order (i, j, k); only
+ * its fiber level enters the sum: fiber f (one stored (i, j) pair) owns the
+ * entries eptr[f] .. eptr[f+1]-1 with third indices eidx[p] and values
+ * vals[p].  The result is kept on A's stored fibers, one dense row per fiber:
+ *   Yf[f, l] = sum_{p in fiber f} vals[p] * X1[eidx[p], l]
+ * (rows of Y without a stored fiber are zero and are not materialised; the
+ * caller's slice pointer and second-index arrays say which (i, j) a row
+ * belongs to).  The reduction, along the sparse index k, is the one of SpMM
+ * (Section 2.1), so every point of the SpMM design space applies.
+ *   F         number of stored fibers
+ *   K, L      extent of the contracted index, columns of X1 and Yf
+ *   eptr      device, F+1 int32, eptr[0] = 0, non-decreasing
+ *   eidx      device, eptr[F] int32 in [0, K)
+ *   vals      device, eptr[F] floats
+ *   X1        device, K x L row-major
+ *   Yf        device, F x L row-major; OVERWRITTEN
+ *   group_size, strategy, schedule, nnz_hint, stream, ownership, errors
+ *             as for sgap_spmm_csr_ex with rows = fibers.
+ */
+int sgap_ttm_csf(int64_t F, int64_t K, int64_t L,
+                 const int32_t* eptr, const int32_t* eidx, const float* vals,
+                 const float* X1, float* Yf,
+                 int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream);
+
+/*
+ * Matricized tensor times Khatri-Rao product, the MTTKRP form of the paper's
+ * Section 2.1 (first form under Eq. 1):
+ *   Y[i, j] = sum_{k, l} A[i, k, l] * X1[k, j] * X2[l, j].
+ * A (I x K x L) is stored as compressed sparse fibers in the index order
+ * (i, k, l): slice i owns the fibers fptr[i] .. fptr[i+1]-1; fiber f has
+ * second index fidx[f] and owns the entries eptr[f] .. eptr[f+1]-1; entry p
+ * has third index eidx[p] and value vals[p].  The operator holds two
+ * reductions of the SpMM kind, the first over the entries of a fiber, the
+ * second over the fibers of a slice, whose input is the first one's output
+ * (Section 2.1); both are served by the segment-group primitives.
+ *   fptr      device, I+1 int32, fptr[0] = 0, non-decreasing
+ *   fidx      device, fptr[I] int32 in [0, K)
+ *   eptr      device, fptr[I]+1 int32, eptr[0] = 0, non-decreasing
+ *   eidx      device, eptr[fptr[I]] int32 in [0, L)
+ *   vals      device, as many floats
+ *   X1, X2    device, K x J and L x J row-major
+ *   Y         device, I x J row-major; OVERWRITTEN
+ *   group_size, strategy
+ *             SGAP_REDUCE_PARALLEL: group_size lanes share a slice, split its
+ *             fibers between them and tree-sum once per slice;
+ *             SGAP_REDUCE_SERIAL: one lane (per column chunk) works through
+ *             group_size consecutive slices by itself.
+ * Slices are the unit of work (row-split schedule): every element of Y has
+ * one writer, no atomics, empty slices are written as zeros, results are
+ * reproducible run to run.  Indices need not be sorted or distinct.
+ * Asynchronous on `stream`; ownership and errors as for sgap_spmm_csr.
+ * I == 0 or J == 0 returns at once.  fidx, eptr, eidx and vals may be null
+ * only for a tensor without fibers (every fptr[i] = 0): they are read only
+ * for fibers that fptr announces, which the host cannot check.
+ */
+int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J,
+                    const int32_t* fptr, const int32_t* fidx,
+                    const int32_t* eptr, const int32_t* eidx, const float* vals,
+                    const float* X1, const float* X2, float* Y,
+                    int group_size, int strategy, void* stream);
+
+/*
  * Tuner over the design space: the paper closes (Section 8) by proposing that
  * the space be exposed as an auto-tuning interface, and Table 5 measures what
  * a per-matrix choice gains over the best fixed point.  Times every

@@ -39,6 +39,8 @@ EXPORTS = {
     "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
     "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
     "sgap_sddmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
+    "sgap_ttm_csf": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
+    "sgap_mttkrp_csf": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
@@ -204,6 +206,35 @@ def sgap_sddmm_csr(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size,
         _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"),
         _dev_ptr(X2T, torch.float32, "X2T"), _dev_ptr(out_vals, torch.float32, "out_vals"),
         int(group_size), int(strategy), int(nnz_hint), _stream_ptr(stream)))
+
+
+def sgap_ttm_csf(F, K, L, eptr, eidx, vals, X1, Yf, group_size, strategy, schedule, nnz_hint=None,
+                 stream=None) -> None:
+    """Yf[f, :] = sum over the entries p of fiber f of vals[p] * X1[eidx[p], :] (see include/sgap.h)."""
+    ptrs = _spmm_args(F, K, L, eptr, eidx, vals, X1, Yf)
+    if nnz_hint is None:
+        nnz_hint = eidx.numel()
+    _check(load().sgap_ttm_csf(F, K, L, *ptrs, int(group_size), int(strategy), int(schedule), int(nnz_hint),
+                               _stream_ptr(stream)))
+
+
+def sgap_mttkrp_csf(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, group_size, strategy, stream=None) -> None:
+    """Y[i, j] = sum over the stored (i, k, l) of A[i,k,l] * X1[k, j] * X2[l, j] (see include/sgap.h)."""
+    import torch
+
+    if fptr.numel() != I + 1:
+        raise ValueError("fptr must have I+1 entries")
+    if eptr.numel() != fidx.numel() + 1:
+        raise ValueError("eptr must have one entry more than fidx")
+    if eidx.numel() != vals.numel():
+        raise ValueError("eidx and vals must have the same length")
+    if X1.numel() != K * J or X2.numel() != L * J or Y.numel() != I * J:
+        raise ValueError("X1 must hold K*J, X2 L*J and Y I*J elements")
+    _check(load().sgap_mttkrp_csf(
+        I, K, L, J, _dev_ptr(fptr, torch.int32, "fptr"), _dev_ptr(fidx, torch.int32, "fidx"),
+        _dev_ptr(eptr, torch.int32, "eptr"), _dev_ptr(eidx, torch.int32, "eidx"),
+        _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"), _dev_ptr(X2, torch.float32, "X2"),
+        _dev_ptr(Y, torch.float32, "Y"), int(group_size), int(strategy), _stream_ptr(stream)))
 
 
 class PointTime(ctypes.Structure):

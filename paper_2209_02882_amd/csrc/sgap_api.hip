@@ -326,6 +326,57 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     return SGAP_OK;
 }
 
+int sgap_ttm_csf(int64_t F, int64_t K, int64_t L, const int32_t* eptr, const int32_t* eidx, const float* vals,
+                 const float* X1, float* Yf, int group_size, int strategy, int schedule, int64_t nnz_hint,
+                 void* stream)
+{
+    // the reduction over the entries of a fiber is the SpMM reduction over the entries of a row
+    return spmm_impl(F, K, L, eptr, eidx, vals, X1, Yf, group_size, strategy, schedule, nnz_hint, stream);
+}
+
+int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* fptr, const int32_t* fidx,
+                    const int32_t* eptr, const int32_t* eidx, const float* vals, const float* X1, const float* X2,
+                    float* Y, int group_size, int strategy, void* stream)
+{
+    using namespace sgap;
+    if (I < 0 || K < 0 || L < 0 || J < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
+    if (I > 2147483646LL || K > 2147483647LL || L > 2147483647LL || J > 2147483647LL)
+        return fail(SGAP_ERR_INVALID_ARG, "dimension exceeds int32 index range");
+    if (!is_pow2_group(group_size)) return fail(SGAP_ERR_INVALID_ARG, "group_size must be 1,2,4,8,16,32 or 64");
+    if (strategy != SGAP_REDUCE_PARALLEL && strategy != SGAP_REDUCE_SERIAL)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
+    if (I == 0 || J == 0) return SGAP_OK;
+    if (!fptr || !Y) return fail(SGAP_ERR_INVALID_ARG, "fptr and Y must not be null");
+    if (K > 0 && L > 0 && (!X1 || !X2)) return fail(SGAP_ERR_INVALID_ARG, "X1 and X2 must not be null");
+    // (fidx, eptr, eidx and vals are read only for fibers that fptr announces)
+
+    const uintptr_t align_bits =
+        reinterpret_cast<uintptr_t>(X1) | reinterpret_cast<uintptr_t>(X2) | reinterpret_cast<uintptr_t>(Y);
+    int vec = 1;
+    if (J % 4 == 0 && (align_bits & 15) == 0) vec = 4;
+    else if (J % 2 == 0 && (align_bits & 7) == 0) vec = 2;
+    const bool par = strategy == SGAP_REDUCE_PARALLEL;
+    const int g = par ? group_size : 1;
+    const int lc = pow2_ceil_capped((J + vec - 1) / vec, 64 / g);
+    // parallel: a group takes one slice at a time (two where groups are wide and a
+    // workgroup would otherwise hold only a few slices); serial: group_size slices per lane
+    const int rows_per_slot = par ? (g * lc >= 64 ? 2 : 1) : group_size;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    auto mark = [&](hipEvent_t& ev) {
+        if (g_profile && hipEventCreate(&ev) == hipSuccess) hipEventRecord(ev, s);
+    };
+    mark(ev0);
+    hipError_t err = launch_mttkrp(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, g, rows_per_slot, par, lc, vec,
+                                   g_xcd_remap == 0 ? 1 : kXcds, s);
+    if (ev0) {
+        mark(ev1);
+        if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);
+    }
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
 int sgap_autotune_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
                       const float* vals, const float* B, float* C, int64_t nnz_hint, int reps, sgap_point_time* table,
                       sgap_point_time* best, void* stream)

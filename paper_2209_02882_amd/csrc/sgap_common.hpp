@@ -184,6 +184,13 @@ hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, 
 // row_cache lets the parallel strategy keep rows of X1 in registers where the shape allows.
 hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec, bool row_cache,
                         int compute_units, int64_t nnz_hint, hipStream_t stream);
+// MTTKRP on compressed sparse fibers: g lanes per slice (1 for the serial
+// strategy), rows_per_slot slices per group (consecutive, or interleaved with
+// the other groups' slices), lc chunk lanes of vec columns each.
+hipError_t launch_mttkrp(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* fptr, const int32_t* fidx,
+                         const int32_t* eptr, const int32_t* eidx, const float* vals, const float* X1,
+                         const float* X2, float* Y, int g, int rows_per_slot, bool interleave, int lc, int vec,
+                         int xcds, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s);

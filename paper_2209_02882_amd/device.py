@@ -74,3 +74,41 @@ class DeviceProblem:
         self.launch(C, group, strategy, schedule, nnz_hint=nnz_hint)
         torch.cuda.synchronize()
         return C
+
+
+class DeviceTensor3:
+    """A Tensor3Problem uploaded into HBM, with launchers for MTTKRP and for TTM
+    along the third index."""
+
+    def __init__(self, p, device="cuda:0"):
+        self.p = p
+        dev = torch.device(device)
+        for name in ("fptr", "fidx", "eptr", "eidx", "vals", "X1", "X2"):
+            setattr(self, name, torch.from_numpy(getattr(p, name)).to(dev))
+
+    def launch_mttkrp(self, Y, group, strategy, stream=None):
+        p = self.p
+        binding.sgap_mttkrp_csf(p.I, p.K, p.L, p.J, self.fptr, self.fidx, self.eptr, self.eidx, self.vals,
+                                self.X1, self.X2, Y, group, binding.STRATEGIES[strategy], stream=stream)
+
+    def run_mttkrp(self, group, strategy, poison=True):
+        Y = torch.empty((self.p.I, self.p.J), dtype=torch.float32, device=self.fptr.device)
+        if poison:
+            Y.fill_(float("nan"))
+        self.launch_mttkrp(Y, group, strategy)
+        torch.cuda.synchronize()
+        return Y
+
+    def launch_ttm(self, Yf, group, strategy, schedule, stream=None):
+        """Yf[f, :] = sum over fiber f's entries of vals * X2[eidx, :] (X2 serves as TTM's dense operand)."""
+        p = self.p
+        binding.sgap_ttm_csf(p.fibers, p.L, p.J, self.eptr, self.eidx, self.vals, self.X2, Yf, group,
+                             binding.STRATEGIES[strategy], binding.SCHEDULES[schedule], stream=stream)
+
+    def run_ttm(self, group, strategy, schedule, poison=True):
+        Yf = torch.empty((self.p.fibers, self.p.J), dtype=torch.float32, device=self.fptr.device)
+        if poison:
+            Yf.fill_(float("nan"))
+        self.launch_ttm(Yf, group, strategy, schedule)
+        torch.cuda.synchronize()
+        return Yf
