@@ -47,6 +47,12 @@ MEASURED_SDDMM_TRAFFIC_BYTES: dict = {
 }
 
 
+# the same for --op mttkrp / ttm, keyed by (op, workload, point...)
+MEASURED_TENSOR_TRAFFIC_BYTES: dict = {
+    ("mttkrp", "tensor3", 8, "parallel"): 2_019_630_322,   # profiles/mttkrp_kernel_tensor3.md
+}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -265,10 +271,142 @@ def main_sddmm(a):
     print(json.dumps(out), flush=True)
 
 
+def main_tensor(a):
+    """--op mttkrp / --op ttm: the third-order operators on a seeded random
+    tensor (--workload tensor3 unless another tensor workload is named), same
+    JSON contract.  TTM along the third index is SpMM over the stored fibers,
+    so it sweeps all 28 SpMM points; MTTKRP sweeps (group_size, strategy)."""
+    import torch
+
+    import numpy as np
+
+    from paper_2209_02882_amd import binding
+    from paper_2209_02882_amd import workloads as wl
+    from paper_2209_02882_amd.device import POINTS, DeviceTensor3
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.load()
+    name = a.workload if a.workload in wl.TENSOR_WORKLOADS else "tensor3"
+    p = wl.make_tensor3(name, J=a.ncols)
+    log(f"[bench] {a.op} on {name}: {p.stats()}")
+    dt = DeviceTensor3(p)
+    ttm = a.op == "ttm"
+    if ttm:
+        out_t = torch.empty((p.fibers, p.J), dtype=torch.float32, device="cuda:0")
+        min_bytes = p.nnz * 8 + (p.fibers + 1) * 4 + p.L * p.J * 4 + p.fibers * p.J * 4
+        flops = 2 * p.nnz * p.J
+        points = POINTS
+        launch = lambda pt: dt.launch_ttm(out_t, *pt)
+    else:
+        out_t = torch.empty((p.I, p.J), dtype=torch.float32, device="cuda:0")
+        min_bytes = p.mttkrp_minimal_bytes()
+        flops = p.mttkrp_flops()
+        points = [(g, st) for st in ("parallel", "serial") for g in binding.GROUP_SIZES]
+        launch = lambda pt: dt.launch_mttkrp(out_t, *pt)
+
+    def run(pt, n):
+        for _ in range(n):
+            launch(pt)
+
+    sweep = []
+    if a.point:
+        f = a.point.split(",")
+        best = (int(f[0]), *f[1:])
+    else:
+        for pt in points:
+            run(pt, 1)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(pt, a.sweep_iters)
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / a.sweep_iters
+            sweep.append({"point": list(pt), "ms": t * 1e3, "gflops": flops / t / 1e9, "gbs": min_bytes / t / 1e9,
+                          "hbm_frac": min_bytes / t / 1e9 / HBM_PEAK_GBS})
+            log(f"[sweep] {a.op} {pt} {t * 1e3:9.3f} ms {flops / t / 1e9:9.1f} GFLOP/s {min_bytes / t / 1e9:8.1f} GB/s")
+        best = tuple(min(sweep, key=lambda r: r["ms"])["point"])
+    run(best, a.warmup)
+    binding.sgap_profile_enable(True)
+    binding.sgap_profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(best, a.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, n_ev = binding.sgap_profile_collect()
+    binding.sgap_profile_enable(False)
+    ms_per_step = elapsed / a.steps * 1e3
+    kernel_avg_ms = kernel_ms / max(1, n_ev)
+    achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    copy_gbs = copy_reference(torch, binding)
+    config = {"workload": name, "op": a.op, "I": p.I, "K": p.K, "L": p.L, "J": p.J, "fibers": p.fibers,
+              "nnz": p.nnz, "group_size": best[0], "strategy": best[1]}
+    if ttm:
+        config["schedule"] = best[2]
+    out = {
+        "metric": ("TTM effective GFLOP/s (2*nnz*J/t)" if ttm else "MTTKRP effective GFLOP/s (2*(nnz+fibers)*J/t)")
+                  + ", fp32, best point",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": config,
+        "copy_kernel_gbs": copy_gbs,
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TENSOR_TRAFFIC_BYTES.get((a.op, name, *best)) if a.ncols is None else None,
+            "kernel_avg_ms": kernel_avg_ms,
+            "algorithmic_bytes": min_bytes,
+        },
+    }
+    if not a.no_cpu_baseline:
+        import oracle
+
+        cores = len(os.sched_getaffinity(0))
+        env = os.environ.get("OMP_NUM_THREADS")
+        if env and env.isdigit():
+            cores = min(cores, int(env))
+        reps, t_all = 0, 0.0
+        while t_all < 10.0 and reps < 200:
+            t0 = time.perf_counter()
+            if ttm:
+                oracle.ttm_csf(p.I, p.K, p.L, p.J, p.fptr, p.fidx, p.eptr, p.eidx, p.vals, p.X2, nthreads=cores)
+            else:
+                oracle.mttkrp_csf(p.I, p.K, p.L, p.J, p.fptr, p.fidx, p.eptr, p.eidx, p.vals, p.X1, p.X2,
+                                  nthreads=cores)
+            t_all += time.perf_counter() - t0
+            reps += 1
+        out["cpu_baseline"] = {
+            "value": flops * reps / t_all / 1e9,
+            "unit": "GFLOP/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": f"whole {name} workload x{reps}, fp64 {a.op} oracle (result and error bound), static split "
+                      f"over {cores} threads, {t_all:.1f} s; rated with the same flop count as the GPU line",
+            "seconds_per_pass": t_all / reps,
+        }
+    if a.sweep_out and sweep:
+        with open(a.sweep_out, "w") as f:
+            json.dump({"workload": name, "op": a.op, "stats": p.stats(), "points": sweep}, f, indent=1)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm"),
-                    help="spmm (the headline path) or sddmm on the same workload's pattern")
+    ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm", "mttkrp", "ttm"),
+                    help="spmm (the headline path), sddmm on the same workload's pattern, or mttkrp / ttm on a "
+                         "seeded third-order tensor")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
@@ -288,6 +426,8 @@ def main():
 
     if a.op == "sddmm":
         return main_sddmm(a)
+    if a.op in ("mttkrp", "ttm"):
+        return main_tensor(a)
 
     import torch
 

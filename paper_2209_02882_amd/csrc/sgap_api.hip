@@ -360,7 +360,7 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* f
     const int lc = pow2_ceil_capped((J + vec - 1) / vec, 64 / g);
     // parallel: a group takes one slice at a time (two where groups are wide and a
     // workgroup would otherwise hold only a few slices); serial: group_size slices per lane
-    const int rows_per_slot = par ? (g * lc >= 64 ? 2 : 1) : group_size;
+    const int rows_per_slot = !par ? group_size : g_rows_per_slot > 0 ? g_rows_per_slot : (g * lc >= 64 ? 2 : 1);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     auto mark = [&](hipEvent_t& ev) {

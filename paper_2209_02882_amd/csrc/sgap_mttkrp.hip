@@ -76,14 +76,31 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(MttkrpArgs a, int rows_p
             // the lanes of a slot share `row`, so whole slots leave together
             const int64_t row = row_first + (interleave ? slot + (int64_t)r * SLOTS : (int64_t)slot * rows_per_slot + r);
             if (row >= row_last) break;
-            const int32_t f_end = a.fptr[row + 1];
+            const int32_t f_begin = a.fptr[row], f_end = a.fptr[row + 1];
             Vec<VEC> acc;
             acc.zero();
-            for (int32_t f = a.fptr[row] + member; f < f_end; f += G) {
-                const int32_t e_end = a.eptr[f + 1];
+            // (second index, first entry, end) of the member's next fiber, asked for one fiber ahead
+            int32_t f = f_begin + member;
+            int32_t next_k = 0, next_begin = 0, next_end = 0;
+            if (f < f_end) {
+                next_k = a.fidx[f];
+                next_begin = a.eptr[f];
+                next_end = a.eptr[f + 1];
+            }
+            for (; f < f_end; f += G) {
+                const int32_t fiber_k = next_k, e_begin = next_begin, e_end = next_end;
+                if (f + G < f_end) {
+                    next_k = a.fidx[f + G];
+                    next_begin = a.eptr[f + G];
+                    next_end = a.eptr[f + G + 1];
+                }
+                // the fiber's row of X1 travels together with its first entries
+                Vec<VEC> x1;
+                x1.zero();
+                if (k_ok) x1 = load_vec<VEC>(a.X1 + (int64_t)fiber_k * a.J + k);
                 Vec<VEC> t;
                 t.zero();
-                for (int32_t base = a.eptr[f]; base < e_end; base += LC) {
+                for (int32_t base = e_begin; base < e_end; base += LC) {
                     // the LC chunk lanes of this member are all here: one entry each
                     int32_t my_idx = 0, my_val = 0;
                     if (base + chunk < e_end) {
@@ -111,11 +128,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(MttkrpArgs a, int rows_p
                         for (int u = 0; u < D; ++u) t.fma(val[u], b[u]);
                     }
                 }
-                if (k_ok) {
-                    const Vec<VEC> x1 = load_vec<VEC>(a.X1 + (int64_t)a.fidx[f] * a.J + k);
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc.v[i] = __builtin_fmaf(x1.v[i], t.v[i], acc.v[i]);
-                }
+                for (int i = 0; i < VEC; ++i) acc.v[i] = __builtin_fmaf(x1.v[i], t.v[i], acc.v[i]);
             }
             // members without fibers contributed +0; the lanes of a slot meet here
 #pragma unroll

@@ -105,6 +105,31 @@ def test_sddmm_arguments_are_checked_without_launch():
     assert lib.sgap_sddmm_csr(4, 4, 4, None, None, None, None, None, None, 8, 1, 0, None) == 0
 
 
+def test_tensor_arguments_are_checked_without_launch():
+    lib = binding.load()
+    ok = dict(I=4, K=4, L=4, J=4, fptr=0x1000, fidx=0x2000, eptr=0x3000, eidx=0x4000, vals=0x5000, X1=0x6000,
+              X2=0x7000, Y=0x8000, group=8, strategy=0)
+    for kw, msg in [(dict(I=-1), b"negative"), (dict(J=-2), b"negative"), (dict(L=1 << 40), b"int32"),
+                    (dict(group=3), b"group_size"), (dict(group=128), b"group_size"), (dict(strategy=5), b"strategy"),
+                    (dict(fptr=None), b"null"), (dict(Y=None), b"null"), (dict(X1=None), b"null"),
+                    (dict(X2=None), b"null")]:
+        a = dict(ok)
+        a.update(kw)
+        rc = lib.sgap_mttkrp_csf(a["I"], a["K"], a["L"], a["J"], a["fptr"], a["fidx"], a["eptr"], a["eidx"],
+                                 a["vals"], a["X1"], a["X2"], a["Y"], a["group"], a["strategy"], None)
+        assert rc == binding.SGAP_ERR_INVALID_ARG, kw
+        assert msg in lib.sgap_last_error(), kw
+    # nothing to do: no slices, or no columns
+    assert lib.sgap_mttkrp_csf(0, 4, 4, 4, None, None, None, None, None, None, None, None, 8, 0, None) == 0
+    assert lib.sgap_mttkrp_csf(4, 4, 4, 0, None, None, None, None, None, None, None, None, 8, 1, None) == 0
+    # TTM takes the SpMM checks with fibers as rows
+    assert lib.sgap_ttm_csf(-1, 4, 4, None, None, None, None, None, 8, 0, 0, -1, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_ttm_csf(4, 4, 4, 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 8, 0, 9, -1, None) \
+        == binding.SGAP_ERR_INVALID_ARG
+    assert b"schedule" in lib.sgap_last_error()
+    assert lib.sgap_ttm_csf(0, 4, 4, None, None, None, None, None, 8, 0, 0, -1, None) == 0
+
+
 def test_empty_shapes_are_ok_without_launch():
     lib = binding.load()
     assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0
