@@ -37,6 +37,8 @@ MEASURED_TRAFFIC_BYTES: dict = {
     ("rmat", 16, "serial", "nnz_balanced"): 4_398_701_021,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
     ("skewed", 64, "serial", "nnz_balanced"): 59_904_989_739,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
     ("powerlaw", 16, "serial", "nnz_balanced"): 242_820_253,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
+    # --long-row-min 1024: all five kernels of the call, profiles/panel_long_rows_kernel_skewed.md
+    ("skewed", 4, "serial", "row_split", 1024): 7_657_730_804,
 }
 
 
@@ -416,6 +418,10 @@ def main():
     ap.add_argument("--point", default=None, help="fix the point: e.g. 8,parallel,row_split (skips the sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-out", default=None, help="write the per-point sweep table (JSON) to this file")
+    ap.add_argument("--long-row-min", type=int, default=0,
+                    help="row-split schedule: rows of at least this many entries are produced by column windows "
+                         "(SGAP_TUNE_LONG_ROW_MIN; 0 = off)")
+    ap.add_argument("--window-kb", type=int, default=0, help="KiB of B per column window of that path (0 = 2048)")
     ap.add_argument("--gr", action="store_true",
                     help="also sweep the row-split points with the reduction narrower than the tiling "
                          "(group_size lanes per row, sub-groups of reduce_size < group_size merged with atomics)")
@@ -446,6 +452,8 @@ def main():
 
     dp = DeviceProblem(p)
     C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
+    binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, a.long_row_min)
+    binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, a.window_kb)
     min_bytes = p.minimal_bytes()
     flops = p.flops()
 
@@ -520,7 +528,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": a.workload, "M": p.M, "K": p.K, "N": p.N, "nnz": p.nnz,
-                   "group_size": g, "strategy": st, "schedule": sc},
+                   "group_size": g, "strategy": st, "schedule": sc, "long_row_min": a.long_row_min},
         "hbm_gbs_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "copy_kernel_gbs": copy_gbs,
@@ -533,7 +541,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc)) if a.ncols is None else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc) + ((a.long_row_min,) if a.long_row_min else ()))
+            if a.ncols is None and not a.window_kb else None,
             "kernel_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },

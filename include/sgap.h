@@ -313,6 +313,24 @@ int sgap_version(void);
  *                        the current row of X1 in registers when
  *                        J <= 16 * group_size and the operands are 16-byte
  *                        aligned; 0: every entry loads both of its rows.
+ *   SGAP_TUNE_LONG_ROW_MIN  row-split schedule, N % 4 == 0 and 16-byte aligned
+ *                        B and C only: rows of at least this many stored
+ *                        entries (say 1024) are taken out of the row-split
+ *                        kernel and produced by column windows: the columns
+ *                        are cut into windows of about 2 MiB of B, a die works
+ *                        on one window at a time so that its L2 serves the
+ *                        gathers, and every (window, long row) piece is added
+ *                        into C with atomic adds (fp32 rounding then varies
+ *                        between runs, as on the nnz-balanced schedule).
+ *                        Worth it when long rows hold most entries and B is
+ *                        far larger than the L2s.  This path keeps its list of
+ *                        long rows (at most 8192; with more it switches itself
+ *                        off for that call) and their window pointers in a
+ *                        device array of the library, about 8.4 MB per GPU,
+ *                        shared by all calls on that GPU: calls that use it
+ *                        must not overlap on one GPU.  0 (default) = off.
+ *   SGAP_TUNE_PANEL_WINDOW_KB  KiB of B per column window of that path (at most
+ *                        255 windows are made); 0 = automatic (2048).
  */
 typedef enum {
     SGAP_TUNE_TILE_COLS = 0,
@@ -320,7 +338,9 @@ typedef enum {
     SGAP_TUNE_ROWS_PER_GROUP = 2,
     SGAP_TUNE_PERSISTENT = 3,
     SGAP_TUNE_NNZ_TILE = 4,
-    SGAP_TUNE_SDDMM_ROW_CACHE = 5
+    SGAP_TUNE_SDDMM_ROW_CACHE = 5,
+    SGAP_TUNE_LONG_ROW_MIN = 6,
+    SGAP_TUNE_PANEL_WINDOW_KB = 7
 } sgap_tuning_knob;
 int sgap_set_tuning(int knob, int value);
 

@@ -159,6 +159,8 @@ SGAP_TUNE_ROWS_PER_GROUP = 2
 SGAP_TUNE_PERSISTENT = 3
 SGAP_TUNE_NNZ_TILE = 4
 SGAP_TUNE_SDDMM_ROW_CACHE = 5
+SGAP_TUNE_LONG_ROW_MIN = 6
+SGAP_TUNE_PANEL_WINDOW_KB = 7
 
 
 def sgap_set_tuning(knob: int, value: int) -> None:

@@ -99,6 +99,8 @@ int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
 int g_rows_per_slot = 0;
 int g_sddmm_row_cache = 1;  // SDDMM parallel: keep rows of X1 in registers where the shape allows
 int g_nnz_tile = 0;    // nnz-balanced serial: forced tile size, 0 = automatic
+int g_long_row_min = 0;     // row-split: rows of at least this many entries go window by window; 0 = off
+int g_panel_window_kb = 0;  // bytes of B per column window in KiB; 0 = automatic (2 MiB)
 int g_persistent = 0;  // row-split: one workgroup per item keeps the rows in flight on a die close together
 
 bool g_profile = false;
@@ -215,6 +217,11 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
                 err = launch_row_split_partial(a, g, reduce_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus,
                                                g_persistent != 0, s);
             }
+        } else if (g_long_row_min > 0 && vec == 4) {
+            mark(ev0);
+            err = launch_row_split_panels(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus,
+                                          g_persistent != 0, g_long_row_min,
+                                          (int64_t)(g_panel_window_kb > 0 ? g_panel_window_kb : 2048) * 1024, s);
         } else {
             mark(ev0);
             // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
@@ -466,6 +473,14 @@ int sgap_set_tuning(int knob, int value)
             if (value != 0 && value != 256 && value != 512 && value != 1024 && value != 2048)
                 return fail(SGAP_ERR_INVALID_ARG, "nnz tile must be 0, 256, 512, 1024 or 2048");
             g_nnz_tile = value;
+            return SGAP_OK;
+        case SGAP_TUNE_LONG_ROW_MIN:
+            if (value < 0) return fail(SGAP_ERR_INVALID_ARG, "long row threshold must be >= 0");
+            g_long_row_min = value;
+            return SGAP_OK;
+        case SGAP_TUNE_PANEL_WINDOW_KB:
+            if (value < 0 || value > (1 << 20)) return fail(SGAP_ERR_INVALID_ARG, "window size out of range");
+            g_panel_window_kb = value;
             return SGAP_OK;
         case SGAP_TUNE_ROWS_PER_GROUP:
             if (value < 0 || value > 65536) return fail(SGAP_ERR_INVALID_ARG, "rows per group out of range");

@@ -169,6 +169,11 @@ hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_
 // are merged with atomics; C must have been zeroed (launch_nnz_zero_rows, -1)
 hipError_t launch_row_split_partial(const SpmmArgs& a, int g, int r, int lc, int vec, int rows_per_slot,
                                     int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
+// the row-split launch with rows of at least min_len stored entries taken out and
+// produced window by window of about window_bytes of B (sgap_panels.hip); vec must be 4
+hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
+                                   int tile_cols, int xcds, int compute_units, bool persistent, int32_t min_len,
+                                   int64_t window_bytes, hipStream_t s);
 // zero the rows of C that receive atomic adds under a merge block of
 // 2^merge_log2 positions, and the rows without entries; merge_log2 = -1: all rows
 hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, int merge_log2, hipStream_t s);

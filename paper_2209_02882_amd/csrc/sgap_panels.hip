@@ -1,0 +1,317 @@
+// Long rows by column windows: a tiling of the reduction dimension for rows
+// whose gathered operands would otherwise stream from HBM (in the spirit of the
+// paper's Section 7.2, where tiling parameters are tuned apart from the
+// synchronisation granularity).
+//
+// A row of many thousand stored entries gathers as many rows of B from all
+// over the matrix; when B is far larger than an L2 (4 MB per die) every one of
+// them comes from HBM, and a workload whose long rows hold most of the entries
+// runs at the random-gather rate of HBM however the reduction is organised.
+// Rows of B are reused *between* long rows, though: with 5,000 rows of 11,000
+// entries over K = 500,000 columns every row of B is wanted about 110 times.
+// This file cuts the columns into windows of about 2 MB of B and takes the work
+// of the long rows window by window: the item (window w, long row r) is the run
+// of r's entries whose column lies in w (columns are sorted inside a row, so it
+// is one contiguous run).  Die w % 8 takes window w, and its workgroups walk the
+// items window-major, so at any moment a die gathers from one or two windows,
+// which its L2 holds.  Every item adds its partial row into C with atomic adds
+// (the rows were zeroed before), which is what the "Atomics" output strategy of
+// Section 6.2 does for a row that several groups produce.
+//
+// The row-split kernel then produces all other rows and leaves the long ones
+// alone (`RowSkip`).  Everything is decided on the device, so the call stays
+// asynchronous: the list of long rows and the window pointers live in a
+// file-scope device array (one per GPU, shared by all calls on it: calls that
+// use this path must not overlap on one GPU).  When the matrix has more long
+// rows than the list holds, this path does nothing and the row-split kernel
+// takes every row.
+#include "sgap_common.hpp"
+#include "sgap_lane_ops.hpp"
+#include "sgap_row_split_impl.hpp"
+
+namespace sgap {
+
+constexpr int kPanelMaxRows = 8192;    // long rows the list holds
+constexpr int kPanelMaxWindows = 255;  // column windows at most
+
+struct PanelScratch {
+    uint32_t count;     // long rows found (may exceed kPanelMaxRows: then the path is off)
+    uint32_t next[15];  // per die: the next item nobody has taken yet
+    uint32_t pad[48];
+    int32_t rows[kPanelMaxRows];
+    // ptr[i * (windows + 1) + w] = first entry of long row i with column >= w * window_rows
+    int32_t ptr[kPanelMaxRows * (kPanelMaxWindows + 1)];
+};
+
+static __device__ __align__(256) PanelScratch g_panel_scratch;
+
+namespace {
+
+// device address of this GPU's scratch array (the symbol's name is a host-side stand-in)
+PanelScratch* panel_scratch()
+{
+    constexpr int kMaxDevices = 64;
+    static PanelScratch* per_device[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_panel_scratch)) != hipSuccess) return nullptr;
+        per_device[dev] = static_cast<PanelScratch*>(p);
+    }
+    return per_device[dev];
+}
+
+}  // namespace
+
+__global__ void panel_reset_kernel(PanelScratch* scr)
+{
+    if (blockIdx.x == 0 && threadIdx.x < 16) (&scr->count)[threadIdx.x] = 0;  // count and next[]
+}
+
+__global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, PanelScratch* scr, int32_t min_len)
+{
+    const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (row >= a.M) return;
+    if (a.rowptr[row + 1] - a.rowptr[row] >= min_len) {
+        const uint32_t i = atomicAdd(&scr->count, 1u);
+        if (i < (uint32_t)kPanelMaxRows) scr->rows[i] = (int32_t)row;
+    }
+}
+
+// Window pointers of the long rows, and zeros in their rows of C.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelScratch* scr, int windows,
+                                                                int32_t window_rows)
+{
+    const uint32_t n = scr->count;
+    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const int64_t threads = (int64_t)gridDim.x * kBlock;
+    const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int per_row = windows + 1;
+    for (int64_t t = tid; t < (int64_t)n * per_row; t += threads) {
+        const int i = (int)(t / per_row), w = (int)(t % per_row);
+        const int32_t row = scr->rows[i];
+        int32_t lo = a.rowptr[row], hi = a.rowptr[row + 1];
+        if (w < windows) {
+            // first entry whose column is >= the window's first column.  For any
+            // order of the columns this is monotone in w, starts at the row's first
+            // entry and (w == windows) ends at its end: the runs always partition the row.
+            const int64_t target = (int64_t)w * window_rows;
+            while (lo < hi) {
+                const int32_t mid = lo + (hi - lo) / 2;
+                if (a.colidx[mid] >= target) hi = mid;
+                else lo = mid + 1;
+            }
+        } else {
+            lo = hi;
+        }
+        scr->ptr[(int64_t)i * per_row + w] = lo;
+    }
+    const int64_t chunks = a.N / VEC;  // N % VEC == 0
+    Vec<VEC> z;
+    z.zero();
+    for (int64_t t = tid; t < (int64_t)n * chunks; t += threads) {
+        const int i = (int)(t / chunks);
+        const int64_t k = (t % chunks) * VEC;
+        store_vec<VEC>(a.C + (int64_t)scr->rows[i] * a.N + k, z);
+    }
+}
+
+constexpr int kPanelDepth = 8;   // gathered rows of B in flight per lane
+constexpr int kPanelClaim = 16;  // items a workgroup takes from its die's counter at a time
+
+// One item: the entries [p0, p1) of row `row`, multiplied out by one wavefront
+// whose 64 lanes are G members x LC chunk lanes: the members split the entries,
+// the group tree-sums and member 0 adds the partial row into C.  p0, p1 and row
+// are the same in all lanes.
+template <int G, int LC, int VEC, bool OFF32>
+__device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_t p1, int64_t row, int lane)
+{
+    constexpr int D = kPanelDepth;
+    const int member = lane / LC;
+    const int chunk = lane % LC;
+    for (int64_t k0 = 0; k0 < a.N; k0 += (int64_t)LC * VEC) {
+        const int64_t k = k0 + (int64_t)chunk * VEC;
+        const bool k_ok = k < a.N;
+        const BRow<OFF32> brow(a.B, a.N, k_ok ? k : 0);
+        Vec<VEC> acc;
+        acc.zero();
+        for (int32_t base = p0; base < p1; base += kWave) {
+            // 64 entries with one coalesced load each for columns and values
+            int32_t my_col = 0, my_val = 0;
+            if (base + lane < p1) {
+                my_col = load_stream(a.colidx + base + lane);
+                my_val = __float_as_int(load_stream(a.vals + base + lane));
+            }
+            const int cnt = p1 - base < kWave ? p1 - base : kWave;
+            // member m takes entries m, m + G, ... of the 64
+            for (int j0 = 0; j0 < cnt; j0 += G * D) {
+                int32_t col[D];
+                float val[D];
+                Vec<VEC> b[D];
+#pragma unroll
+                for (int u = 0; u < D; ++u) {
+                    const int j = j0 + u * G + member;
+                    col[u] = __shfl(my_col, j & (kWave - 1), kWave);
+                    val[u] = __int_as_float(__shfl(my_val, j & (kWave - 1), kWave));
+                    if (j >= cnt) val[u] = 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < D; ++u) {
+                    b[u].zero();
+                    if (k_ok && j0 + u * G + member < cnt) b[u] = load_vec<VEC>(brow.at(col[u]));
+                }
+#pragma unroll
+                for (int u = 0; u < D; ++u) acc.fma(val[u], b[u]);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc.v[v] = group_tree_sum<G, LC>(acc.v[v]);
+        if constexpr (LC >= VEC) {
+            // Member 0's LC lanes hold LC*VEC consecutive columns, VEC per lane.  An
+            // atomic instruction whose lanes are 16 bytes apart keeps the memory
+            // pipeline busy 2.5 times longer than one over consecutive words (290
+            // against 115 clocks, measured), so the sums change hands first: in
+            // round q lane l adds column q*LC + l, which lane (q*LC + l) / VEC holds.
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+                const int col = q * LC + chunk;  // column of this pass, counted from k0
+                float mine = 0.0f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float t = __shfl(acc.v[v], col / VEC, kWave);  // lanes 0 .. LC-1 are member 0
+                    if (col % VEC == v) mine = t;
+                }
+                if (member == 0 && k0 + col < a.N) unsafeAtomicAdd(a.C + row * a.N + k0 + col, mine);
+            }
+        } else {
+            if (member == 0 && k_ok) atomic_add_vec<VEC>(a.C + row * a.N + k, acc);
+        }
+    }
+}
+
+// Die x takes the windows x, x + xcds, ...; its items, window-major, are handed
+// out to its workgroups kPanelClaim at a time from one counter, one item per
+// wavefront.  Items differ in length by a factor of ten and more: with a fixed
+// deal the wavefronts of a die drift more than a window apart, which the L2
+// cannot hold (43 GB fetched instead of 1.8 GB on the skewed workload), and one
+// item per claim makes the counter the bottleneck (a returning atomic on one
+// address takes about 0.1 us).
+template <int G, int LC, int VEC, bool OFF32>
+__global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, PanelScratch* scr, int windows, int xcds)
+{
+    static_assert(G * LC == kWave, "one wavefront per item");
+    __shared__ uint32_t s_claim;
+    const uint32_t n = scr->count;
+    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int per_row = windows + 1;
+    const int xcd = blockIdx.x % xcds;
+    const int64_t my_windows = xcd < windows ? (windows - xcd + xcds - 1) / xcds : 0;
+    const uint32_t items = (uint32_t)(my_windows * n);  // at most 255 * 8192
+    for (;;) {
+        __syncthreads();  // everyone has read the previous claim
+        if (threadIdx.x == 0) s_claim = atomicAdd(&scr->next[xcd], (uint32_t)kPanelClaim);
+        __syncthreads();
+        const uint32_t claim = s_claim;
+        if (claim >= items) break;  // the whole workgroup; the counter only grows, so every workgroup gets here
+        for (int r = 0; r < kPanelClaim / kWavesPerBlock; ++r) {
+            const uint32_t it = claim + (uint32_t)(r * kWavesPerBlock + wave);
+            if (it >= items) break;
+            const int w = xcd + xcds * (int)(it / n);
+            const int i = (int)(it % n);
+            const int32_t p0 = scr->ptr[(int64_t)i * per_row + w];
+            const int32_t p1 = scr->ptr[(int64_t)i * per_row + w + 1];
+            if (p0 < p1) panel_item<G, LC, VEC, OFF32>(a, p0, p1, scr->rows[i], lane);
+        }
+    }
+}
+
+namespace {
+
+template <int G, int LC, int VEC>
+void launch_long_rows(const SpmmArgs& a, PanelScratch* scr, int windows, int xcds, int compute_units,
+                      hipStream_t s)
+{
+    const bool off32 = offsets_fit_32(a);
+    static int per_cu[2] = {0, 0};
+    if (per_cu[off32] == 0) {
+        int n = 0;
+        const hipError_t e =
+            off32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, panel_long_rows_kernel<G, LC, VEC, true>, kBlock, 0)
+                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, panel_long_rows_kernel<G, LC, VEC, false>, kBlock, 0);
+        per_cu[off32] = (e == hipSuccess && n >= 1) ? n : 1;
+    }
+    int grid = per_cu[off32] * compute_units;
+    grid -= grid % xcds;
+    if (grid < xcds) grid = xcds;
+    if (off32)
+        hipLaunchKernelGGL((panel_long_rows_kernel<G, LC, VEC, true>), dim3(grid), dim3(kBlock), 0, s, a, scr, windows,
+                           xcds);
+    else
+        hipLaunchKernelGGL((panel_long_rows_kernel<G, LC, VEC, false>), dim3(grid), dim3(kBlock), 0, s, a, scr, windows,
+                           xcds);
+}
+
+}  // namespace
+
+// Column windows of about window_bytes of B each, at most kPanelMaxWindows.
+void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32_t* window_rows)
+{
+    int64_t rows = window_bytes / (N * 4);
+    if (rows < 1) rows = 1;
+    int64_t w = (K + rows - 1) / rows;
+    if (w > kPanelMaxWindows) {
+        w = kPanelMaxWindows;
+        rows = (K + w - 1) / w;
+        w = (K + rows - 1) / rows;
+    }
+    if (w < 1) w = 1;
+    *windows = (int)w;
+    *window_rows = (int32_t)rows;
+}
+
+// Long rows (at least min_len entries) window by window, all other rows by the
+// row-split kernel with g lanes per row.  Requires vec == 4 (N % 4 == 0, 16-byte
+// aligned B and C).  lc and the other row-split arguments as for launch_row_split.
+hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
+                                   int tile_cols, int xcds, int compute_units, bool persistent, int32_t min_len,
+                                   int64_t window_bytes, hipStream_t s)
+{
+    if (vec != 4 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
+    PanelScratch* scr = panel_scratch();
+    if (!scr) return hipErrorInvalidValue;
+    int windows = 1;
+    int32_t window_rows = 1;
+    plan_panels(a.K, a.N, window_bytes, &windows, &window_rows);
+
+    hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
+    hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
+                       min_len);
+    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, windows,
+                       window_rows);
+    // one wavefront per item: chunk lanes for the columns of one pass, the rest of the 64 lanes split the entries
+    int wave_lc = 1;
+    while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
+    switch (wave_lc) {
+        case 1: launch_long_rows<64, 1, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 2: launch_long_rows<32, 2, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 4: launch_long_rows<16, 4, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 8: launch_long_rows<8, 8, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 16: launch_long_rows<4, 16, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 32: launch_long_rows<2, 32, 4>(a, scr, windows, xcds, compute_units, s); break;
+        default: launch_long_rows<1, 64, 4>(a, scr, windows, xcds, compute_units, s); break;
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+
+    row_split_detail::Launch<false, true> f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units,
+                                            offsets_fit_32(a), persistent, 0, s,
+                                            RowSkip{&scr->count, (uint32_t)kPanelMaxRows, min_len}};
+    if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace sgap

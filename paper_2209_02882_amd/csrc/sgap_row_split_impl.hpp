@@ -11,12 +11,21 @@ namespace sgap {
 constexpr int kStageCap = 2048;  // (column, value) pairs per LDS chunk: 16 KB
 constexpr int kRowCap = 1024;    // rowptr entries kept in LDS per row block (+1)
 
+// Rows another kernel produces: when *count <= max_rows, rows of at least
+// min_len stored entries are neither multiplied out nor written here.
+struct RowSkip {
+    const uint32_t* __restrict__ count;
+    uint32_t max_rows;
+    int32_t min_len;
+};
+
 // PARTIAL: the G members of a row reduce in sub-groups of `reduce_members`
 // (a power of two below G) and the first member of every sub-group adds its
 // sum to C with atomics; C must hold zeros before the launch.
-template <int G, int LC, int VEC, bool OFF32, bool PARTIAL>
+// SKIP: leave the rows described by `skip` alone.
+template <int G, int LC, int VEC, bool OFF32, bool PARTIAL, bool SKIP = false>
 __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot,
-                                                           int interleave, int reduce_members)
+                                                           int interleave, int reduce_members, RowSkip skip)
 {
     __shared__ StagedEntry s_A[kStageCap];
     __shared__ int32_t s_rp[kRowCap + 1];
@@ -29,6 +38,8 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
     const int64_t N = a.N;
     const int64_t rows_per_block = (int64_t)SLOTS * rows_per_slot;
     const bool rp_in_lds = rows_per_block <= kRowCap;
+    bool skip_on = false;
+    if constexpr (SKIP) skip_on = *skip.count <= skip.max_rows;
 
     // persistent walk over this die's run of work items
     const int64_t xcd = blockIdx.x % ts.xcds;
@@ -88,7 +99,9 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                     }
                     const uint32_t lo = p_begin > base ? p_begin : base;
                     const uint32_t hi = p_end < base + cnt ? p_end : base + cnt;
-                    if (k_ok && lo < hi) {
+                    bool skipped = false;
+                    if constexpr (SKIP) skipped = skip_on && p_end - p_begin >= (uint32_t)skip.min_len;
+                    if (!skipped && k_ok && lo < hi) {
                         // first position >= lo that belongs to this member
                         const uint32_t first = lo + ((member - (lo - p_begin)) & (G - 1));
                         if (first < hi) gather_fma<VEC, G>(acc, s_A, first - base, hi - base, Brow);
@@ -106,7 +119,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
-                        if (member == 0 && k_ok) store_vec_stream<VEC>(a.C + (row_first + row) * N + k, acc);
+                        if (member == 0 && k_ok && !skipped) store_vec_stream<VEC>(a.C + (row_first + row) * N + k, acc);
                     }
                     acc.zero();
                     row += row_step;
@@ -119,13 +132,14 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
 
 namespace row_split_detail {
 
-template <bool PARTIAL>
+template <bool PARTIAL, bool SKIP = false>
 struct Launch {
     const SpmmArgs& a;
     int rows_per_slot, interleave, tile_cols, xcds, compute_units;
     bool off32, persistent;
     int reduce_members;
     hipStream_t s;
+    RowSkip skip = {nullptr, 0, 0};
 
     // workgroups of this instance that one compute unit can hold at once
     template <typename K>
@@ -140,8 +154,8 @@ struct Launch {
     void operator()() const
     {
         // a persistent grid must be resident all at once
-        static const int per_cu_32 = resident_per_cu(row_split_kernel<G, LC, VEC, true, PARTIAL>);
-        static const int per_cu_64 = resident_per_cu(row_split_kernel<G, LC, VEC, false, PARTIAL>);
+        static const int per_cu_32 = resident_per_cu(row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>);
+        static const int per_cu_64 = resident_per_cu(row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>);
         const int max_grid = persistent ? compute_units * (off32 ? per_cu_32 : per_cu_64) : 0x7fffffff;
         constexpr int slots = kBlock / (G * LC);
         const int64_t rows_per_block = (int64_t)slots * rows_per_slot;
@@ -157,11 +171,11 @@ struct Launch {
         if (wgs_per_xcd > ts.items_per_xcd) wgs_per_xcd = ts.items_per_xcd;
         const unsigned grid = (unsigned)(wgs_per_xcd * xcds);
         if (off32)
-            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true, PARTIAL>), dim3(grid), dim3(kBlock), 0, s, a,
-                               ts, rows_per_slot, interleave, reduce_members);
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>), dim3(grid), dim3(kBlock), 0, s, a,
+                               ts, rows_per_slot, interleave, reduce_members, skip);
         else
-            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false, PARTIAL>), dim3(grid), dim3(kBlock), 0, s, a,
-                               ts, rows_per_slot, interleave, reduce_members);
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>), dim3(grid), dim3(kBlock), 0, s, a,
+                               ts, rows_per_slot, interleave, reduce_members, skip);
     }
 };
 

@@ -1,0 +1,128 @@
+"""GPU parity of the row-split schedule with long rows taken window by window
+(SGAP_TUNE_LONG_ROW_MIN), against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_02882_amd import binding
+from paper_2209_02882_amd import workloads as wl
+
+from gpu_util import TOL, DeviceProblem, assert_close, full_reference, sample_rows
+from test_gpu_parity import csr_problem
+
+pytestmark = pytest.mark.gpu
+
+ROW_SPLIT_POINTS = [(g, st, "row_split") for st in ("parallel", "serial") for g in binding.GROUP_SIZES]
+
+
+@pytest.fixture
+def panels():
+    """Set the two knobs for a test and restore the defaults afterwards."""
+    def set_knobs(min_len, window_kb=0):
+        binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, min_len)
+        binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, window_kb)
+    yield set_knobs
+    binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, 0)
+    binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, 0)
+
+
+def mixed_lengths(M, K, seed, long_every=17, long_len=(200, 900)):
+    rng = np.random.default_rng(seed)
+    lengths = rng.integers(0, 12, size=M)
+    idx = np.arange(3, M, long_every)
+    lengths[idx] = rng.integers(long_len[0], min(long_len[1], K) + 1, size=idx.size)
+    return lengths
+
+
+@pytest.mark.parametrize("N", [4, 8, 32, 64, 128, 256, 260, 512])
+def test_long_rows_by_windows_match_the_oracle(panels, N):
+    M, K = 1500, 4000
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, N), seed=N, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for window_kb in (0, 64, 1):  # one window, a few dozen, the maximum of 255
+        panels(100, window_kb)
+        for point in ROW_SPLIT_POINTS:
+            assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"N={N} window {window_kb} KiB {point}")
+
+
+def test_float_values_within_tolerance_and_repeatable_within_it(panels):
+    M, K, N = 3000, 20000, 64
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, 5, long_len=(1000, 6000)), seed=5)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    panels(512, 256)
+    for _ in range(3):
+        for point in [(1, "serial", "row_split"), (8, "parallel", "row_split")]:
+            assert_close(dp.run(*point), C_ref, BND, what=f"float {point}")
+
+
+def test_thresholds_at_the_edges(panels):
+    M, K, N = 700, 900, 32
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, 7, long_len=(100, 100)), seed=7, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    # rows exactly at the threshold are long; a threshold above every row leaves all to the row-split kernel;
+    # threshold 1 makes every non-empty row long
+    for min_len in (100, 101, 1):
+        panels(min_len, 16)
+        for point in [(4, "parallel", "row_split"), (2, "serial", "row_split")]:
+            assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"min_len={min_len} {point}")
+
+
+def test_more_long_rows_than_the_list_holds_switches_the_path_off(panels):
+    M, K, N = 9000, 300, 16  # every row is long under min_len = 2: more than 8192
+    p = csr_problem("many_long", M, K, N, np.full(M, 5), seed=3, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    panels(2, 4)
+    for point in [(4, "parallel", "row_split"), (8, "serial", "row_split")]:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"overflow {point}")
+
+
+def test_unsorted_and_repeated_columns_still_add_up(panels):
+    M, K, N = 400, 2000, 32
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, 11), seed=11, integer=True)
+    rng = np.random.default_rng(12)
+    for i in range(M):
+        a, b = p.rowptr[i], p.rowptr[i + 1]
+        perm = rng.permutation(b - a)
+        p.colidx[a:b] = p.colidx[a:b][perm]
+        p.vals[a:b] = p.vals[a:b][perm]
+        if b - a > 3:
+            p.colidx[a + 2] = p.colidx[a]
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    panels(100, 8)
+    for point in [(1, "parallel", "row_split"), (16, "parallel", "row_split"), (4, "serial", "row_split")]:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"unsorted {point}")
+
+
+def test_other_schedules_and_unaligned_operands_ignore_the_knob(panels):
+    M, K, N = 500, 1000, 30  # N % 4 != 0: narrower loads, the window path does not apply
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, 13), seed=13, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    panels(100, 8)
+    for point in [(4, "parallel", "row_split"), (8, "serial", "nnz_balanced"), (8, "parallel", "nnz_balanced")]:
+        assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"ignored {point}")
+    with pytest.raises(binding.SgapError):
+        binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, -1)
+
+
+def test_full_size_skewed_sampled_rows(panels):
+    p = wl.make_problem("skewed")
+    dp = DeviceProblem(p)
+    rows = sample_rows(p)
+    C_ref, BND = oracle.spmm_csr_rows(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, rows)
+    rows_t = torch.from_numpy(rows).cuda()
+    C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
+    panels(1024)
+    for point in [(1, "parallel", "row_split"), (4, "parallel", "row_split"), (2, "serial", "row_split")]:
+        print("  point", point, flush=True)
+        dp.run(*point, C=C)
+        assert not torch.isnan(C).any(), f"{point}: element never written"
+        got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
+        bad = np.abs(got - C_ref) > TOL * BND
+        assert not bad.any(), f"{point}: {int(bad.sum())} sampled elements out of tolerance"
