@@ -236,15 +236,15 @@ void launch_long_rows(const SpmmArgs& a, PanelScratch* scr, int windows, int xcd
                       hipStream_t s)
 {
     const bool off32 = offsets_fit_32(a);
-    static int per_cu[2] = {0, 0};
-    if (per_cu[off32] == 0) {
+    // workgroups of each instance that one compute unit holds at once: the grid must be resident as a whole
+    auto resident = [](auto kernel) {
         int n = 0;
-        const hipError_t e =
-            off32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, panel_long_rows_kernel<G, LC, VEC, true>, kBlock, 0)
-                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, panel_long_rows_kernel<G, LC, VEC, false>, kBlock, 0);
-        per_cu[off32] = (e == hipSuccess && n >= 1) ? n : 1;
-    }
-    int grid = per_cu[off32] * compute_units;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n < 1) n = 1;
+        return n;
+    };
+    static const int per_cu_32 = resident(panel_long_rows_kernel<G, LC, VEC, true>);
+    static const int per_cu_64 = resident(panel_long_rows_kernel<G, LC, VEC, false>);
+    int grid = (off32 ? per_cu_32 : per_cu_64) * compute_units;
     grid -= grid % xcds;
     if (grid < xcds) grid = xcds;
     if (off32)
@@ -254,8 +254,6 @@ void launch_long_rows(const SpmmArgs& a, PanelScratch* scr, int windows, int xcd
         hipLaunchKernelGGL((panel_long_rows_kernel<G, LC, VEC, false>), dim3(grid), dim3(kBlock), 0, s, a, scr, windows,
                            xcds);
 }
-
-}  // namespace
 
 // Column windows of about window_bytes of B each, at most kPanelMaxWindows.
 void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32_t* window_rows)
@@ -272,6 +270,8 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
     *windows = (int)w;
     *window_rows = (int32_t)rows;
 }
+
+}  // namespace
 
 // Long rows (at least min_len entries) window by window, all other rows by the
 // row-split kernel with g lanes per row.  Requires vec == 4 (N % 4 == 0, 16-byte

@@ -126,3 +126,31 @@ def test_full_size_skewed_sampled_rows(panels):
         got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
         bad = np.abs(got - C_ref) > TOL * BND
         assert not bad.any(), f"{point}: {int(bad.sum())} sampled elements out of tolerance"
+
+
+def test_the_window_path_can_be_captured_in_a_graph_and_replayed(panels):
+    # after one eager call (which looks up the device array's address and the
+    # kernels' occupancy) the path only launches kernels on the caller's stream:
+    # its counters are cleared by a kernel, not by a memset node
+    M, K, N = 1500, 4000, 64
+    p = csr_problem("mixed", M, K, N, mixed_lengths(M, K, 21), seed=21, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    panels(100, 64)
+    points = [(1, "serial", "row_split"), (8, "parallel", "row_split")]
+    outs = [dp.new_output() for _ in points]
+    for C, pt in zip(outs, points):
+        dp.launch(C, *pt)  # eager warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for C, pt in zip(outs, points):
+            dp.launch(C, *pt, stream=torch.cuda.current_stream())
+    for replay in range(3):
+        for C in outs:
+            C.fill_(float("nan"))  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for C, pt in zip(outs, points):
+            assert_close(C, C_ref, BND, exact=True, what=f"graph replay {replay} {pt}")

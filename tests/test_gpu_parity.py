@@ -143,7 +143,7 @@ def csr_problem(name, M, K, N, lengths, seed, integer=False):
     return wl.SpmmProblem(name, M, K, N, rowptr, colidx, vals, B)
 
 
-@pytest.mark.parametrize("N", [1, 2, 3, 4, 6, 12, 20, 100, 130, 256, 260])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 6, 12, 20, 100, 130, 256, 260, 515, 1028])
 def test_column_counts_and_vector_widths(N):
     rng = np.random.default_rng(N)
     M, K = 301, 257
