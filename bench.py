@@ -447,6 +447,7 @@ def main():
     t0 = time.perf_counter()
     p = wl.make_problem(a.workload, N=a.ncols)
     log(f"[bench] workload {a.workload}: {p.row_stats()} generated in {time.perf_counter() - t0:.1f}s")
+    log(f"[bench] recipe: {wl.recipe(a.workload)}; seed {wl.WORKLOADS[a.workload][0]}")
 
     from paper_2209_02882_amd.device import POINTS, DeviceProblem
 

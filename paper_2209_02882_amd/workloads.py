@@ -30,6 +30,8 @@ __all__ = [
     "skewed_rows",
     "fill_values",
     "dense_operand",
+    "RECIPES",
+    "recipe",
     "Tensor3Problem",
     "make_tensor3",
     "TENSOR_WORKLOADS",
@@ -242,6 +244,23 @@ WORKLOADS = {
     "rmat": (1004, 32),
     "skewed": (1005, 256),
 }
+
+# one line per workload on how it is drawn (printed by the benchmark next to the measured statistics)
+RECIPES = {
+    "uniform10": "exactly 10 uniform distinct columns per row",
+    "uniform10_int": "exactly 10 uniform distinct columns per row; values and B uniform on {-2..2}",
+    "powerlaw": "row lengths Zipf-Mandelbrot P(l) ~ (l+q)^-2.1 on [1,4096] with the shift q = %.3f that gives mean 16 "
+                "(a plain Zipf(2.1) has mean 4); columns uniform distinct",
+    "stencil27": "27-point stencil on a cube in natural order, faces clipped; random values",
+    "rmat": "R-MAT (0.57, 0.19, 0.19, 0.05), no permutation, no noise, self loops kept, duplicates removed",
+    "skewed": "1 % of the rows, at seeded random positions, hold 2,000-20,000 entries, the rest 1-8; columns uniform distinct",
+}
+
+
+def recipe(name: str) -> str:
+    text = RECIPES[name]
+    return text % _zipf_mandelbrot_shift(2.1, 1, 4096, 16.0) if "%" in text else text
+
 
 # raw R-MAT edge count whose de-duplicated size is 50M +- 2% at scale 21
 RMAT_SCALE = 21
