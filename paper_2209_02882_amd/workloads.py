@@ -259,7 +259,7 @@ RECIPES = {
 
 def recipe(name: str) -> str:
     text = RECIPES[name]
-    return text % _zipf_mandelbrot_shift(2.1, 1, 4096, 16.0) if "%" in text else text
+    return text % _zipf_mandelbrot_shift(2.1, 1, 4096, 16.0) if "%.3f" in text else text
 
 
 # raw R-MAT edge count whose de-duplicated size is 50M +- 2% at scale 21

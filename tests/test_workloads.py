@@ -83,3 +83,9 @@ def test_distinct_columns_when_rows_are_nearly_full():
     assert list(colidx[:5]) == [0, 1, 2, 3, 4]
     with pytest.raises(ValueError):
         wl.csr_from_lengths(rng, np.array([6]), 5)
+
+
+def test_every_workload_has_a_recipe_line():
+    for name in wl.WORKLOADS:
+        assert isinstance(wl.recipe(name), str) and wl.recipe(name)
+    assert "2.838" in wl.recipe("powerlaw")
