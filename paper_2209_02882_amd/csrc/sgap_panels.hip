@@ -168,25 +168,23 @@ __device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc.v[v] = group_tree_sum<G, LC>(acc.v[v]);
-        if constexpr (LC >= VEC) {
-            // Member 0's LC lanes hold LC*VEC consecutive columns, VEC per lane.  An
-            // atomic instruction whose lanes are 16 bytes apart keeps the memory
-            // pipeline busy 2.5 times longer than one over consecutive words (290
-            // against 115 clocks, measured), so the sums change hands first: in
-            // round q lane l adds column q*LC + l, which lane (q*LC + l) / VEC holds.
+        // Member 0's LC lanes hold the LC*VEC consecutive columns of this pass, VEC per
+        // lane.  An atomic instruction whose lanes are 16 bytes apart keeps the memory
+        // pipeline busy 2.5 times longer than one over consecutive words (290 against
+        // 115 clocks, measured), so the sums change hands first, which also makes the
+        // instructions as few as they can be: in round q lane l adds column q*64 + l,
+        // which lane (q*64 + l) / VEC holds (lanes 0 .. LC-1 are member 0).
+        constexpr int PASS = LC * VEC;
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) {
-                const int col = q * LC + chunk;  // column of this pass, counted from k0
-                float mine = 0.0f;
+        for (int q = 0; q < (PASS + kWave - 1) / kWave; ++q) {
+            const int col = q * kWave + lane;  // column of this pass, counted from k0
+            float mine = 0.0f;
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const float t = __shfl(acc.v[v], col / VEC, kWave);  // lanes 0 .. LC-1 are member 0
-                    if (col % VEC == v) mine = t;
-                }
-                if (member == 0 && k0 + col < a.N) unsafeAtomicAdd(a.C + row * a.N + k0 + col, mine);
+            for (int v = 0; v < VEC; ++v) {
+                const float t = __shfl(acc.v[v], (col / VEC) & (kWave - 1), kWave);
+                if (col % VEC == v) mine = t;
             }
-        } else {
-            if (member == 0 && k_ok) atomic_add_vec<VEC>(a.C + row * a.N + k, acc);
+            if (col < PASS && k0 + col < a.N) unsafeAtomicAdd(a.C + row * a.N + k0 + col, mine);
         }
     }
 }
