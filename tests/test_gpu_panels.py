@@ -154,3 +154,28 @@ def test_the_window_path_can_be_captured_in_a_graph_and_replayed(panels):
         torch.cuda.synchronize()
         for C, pt in zip(outs, points):
             assert_close(C, C_ref, BND, exact=True, what=f"graph replay {replay} {pt}")
+
+
+def test_wide_matrix_offsets_need_64_bits(panels):
+    # K*N*4 >= 2^32: offsets into B do not fit 32 bits, in the window kernel as in the row-split kernel
+    K, N, M = 1 << 22, 256, 300
+    rng = np.random.default_rng(23)
+    lengths = mixed_lengths(M, K, 23, long_every=29, long_len=(300, 2500))
+    rowptr, colidx = wl.csr_from_lengths(rng, lengths, K)
+    colidx[-1] = K - 1  # the far end of B is touched
+    vals = wl.fill_values(rng, colidx.size, True)
+    rows_used = np.unique(colidx)
+    Bsmall = wl.fill_values(rng, rows_used.size * N, True).reshape(-1, N)
+    B = torch.zeros((K, N), dtype=torch.float32, device="cuda:0")
+    B[torch.from_numpy(rows_used.astype(np.int64)).cuda()] = torch.from_numpy(Bsmall).cuda()
+    # oracle on a compacted copy (same rows of B, renumbered columns: the order inside a row is kept)
+    remap = np.searchsorted(rows_used, colidx).astype(np.int32)
+    C_ref, BND = oracle.spmm_csr(M, rows_used.size, N, rowptr, remap, vals, Bsmall)
+    rp, ci, va = (torch.from_numpy(x).cuda() for x in (rowptr, colidx, vals))
+    panels(256)
+    for point in [(1, "serial", "row_split"), (8, "parallel", "row_split")]:
+        C = torch.full((M, N), float("nan"), device="cuda:0")
+        binding.sgap_spmm_csr_ex(M, K, N, rp, ci, va, B, C, point[0], binding.STRATEGIES[point[1]],
+                                 binding.SCHEDULES[point[2]])
+        torch.cuda.synchronize()
+        assert_close(C, C_ref, BND, exact=True, what=f"64-bit offsets {point}")

@@ -146,3 +146,25 @@ def test_ttm_full_size():
                       (2, "serial", "row_split")]:
         print("  ttm full size", g, st, sc, flush=True)
         assert_close(dt.run_ttm(g, st, sc), ref, bnd, what=f"ttm tensor3 g={g} {st} {sc}")
+
+
+def test_mttkrp_wide_factor_offsets_need_64_bits():
+    # L*J*4 >= 2^32: offsets into X2 do not fit 32 bits, the fast address path must not be taken
+    I, K, L, J = 200, 50, 1 << 22, 256
+    rng = np.random.default_rng(31)
+    p = tensor_from(I, K, L, J, rng.integers(0, 5, size=I), [1, 2, 7, 3], 31, integer=True)
+    p.eidx[-1] = L - 1  # the far end of X2 is touched
+    rows_used = np.unique(p.eidx)
+    X2small = wl.fill_values(rng, rows_used.size * J, True).reshape(-1, J)
+    X2 = torch.zeros((L, J), dtype=torch.float32, device="cuda:0")
+    X2[torch.from_numpy(rows_used.astype(np.int64)).cuda()] = torch.from_numpy(X2small).cuda()
+    # oracle on a compacted copy (same rows of X2, renumbered third indices)
+    remap = np.searchsorted(rows_used, p.eidx).astype(np.int32)
+    ref, bnd = oracle.mttkrp_csf(I, K, rows_used.size, J, p.fptr, p.fidx, p.eptr, remap, p.vals, p.X1, X2small)
+    dev = {n: torch.from_numpy(getattr(p, n)).cuda() for n in ("fptr", "fidx", "eptr", "eidx", "vals", "X1")}
+    for g, st in [(1, "parallel"), (8, "parallel"), (64, "parallel"), (4, "serial")]:
+        Y = torch.full((I, J), float("nan"), device="cuda:0")
+        binding.sgap_mttkrp_csf(I, K, L, J, dev["fptr"], dev["fidx"], dev["eptr"], dev["eidx"], dev["vals"], dev["X1"],
+                                X2, Y, g, binding.STRATEGIES[st])
+        torch.cuda.synchronize()
+        assert_close(Y, ref, bnd, exact=True, what=f"64-bit offsets g={g} {st}")
