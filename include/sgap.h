@@ -394,6 +394,28 @@ int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_ti
 int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
                                int compute_units, int forced_tile, int* tile, int* merge_on_chip);
 
+/*
+ * Check the preconditions that the compute calls rely on and cannot test
+ * themselves (the paper's Section 2.2 takes a well-formed CSR for granted).
+ * Debugging aid: it runs three small kernels and then WAITS for `stream`.
+ *   nnz       the length of colidx (required here: a damaged rowptr must not
+ *             decide how far colidx is read)
+ *   report    host, 4 counters:
+ *             [0] defects of rowptr: rowptr[0] != 0, rowptr[M] != nnz, and
+ *                 every i with rowptr[i] > rowptr[i+1]
+ *             [1] stored entries whose column is outside [0, K)
+ *             [2] stored entries that are not larger than their predecessor
+ *                 in the same row (unsorted or repeated columns: allowed, all
+ *                 kernels just add; counted only when [0] is zero, else -1)
+ *             [3] rows without stored entries (information; -1 unless [0] is zero)
+ * Returns SGAP_OK when the check ran (whatever it found), SGAP_ERR_INVALID_ARG
+ * for null pointers with non-zero extents or negative sizes.  The counters
+ * live in a small device array of the library: calls must not overlap on one
+ * GPU.
+ */
+int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, int64_t nnz,
+                      int64_t* report, void* stream);
+
 /* Plain device-to-device fp32 copy kernel (n elements).  Used to calibrate
  * hardware traffic counters and to report a streaming-bandwidth reference. */
 int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream);

@@ -39,6 +39,7 @@ EXPORTS = {
     "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
     "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
     "sgap_sddmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
+    "sgap_validate_csr": (_int, [_i64, _i64, _p, _p, _i64, _p, _p]),
     "sgap_ttm_csf": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_mttkrp_csf": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
@@ -237,6 +238,21 @@ def sgap_mttkrp_csf(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, group_s
         _dev_ptr(eptr, torch.int32, "eptr"), _dev_ptr(eidx, torch.int32, "eidx"),
         _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"), _dev_ptr(X2, torch.float32, "X2"),
         _dev_ptr(Y, torch.float32, "Y"), int(group_size), int(strategy), _stream_ptr(stream)))
+
+
+def sgap_validate_csr(M, K, rowptr, colidx, stream=None):
+    """Counts of (rowptr defects, columns out of range, unsorted or repeated
+    columns, empty rows) of a CSR matrix in device memory; the last two are -1
+    when rowptr is damaged.  Waits for the stream (see include/sgap.h)."""
+    import torch
+
+    if rowptr.numel() != M + 1:
+        raise ValueError("rowptr must have M+1 entries")
+    report = (ctypes.c_int64 * 4)()
+    _check(load().sgap_validate_csr(M, K, _dev_ptr(rowptr, torch.int32, "rowptr"),
+                                    _dev_ptr(colidx, torch.int32, "colidx"), colidx.numel(), report,
+                                    _stream_ptr(stream)))
+    return tuple(report)
 
 
 class PointTime(ctypes.Structure):

@@ -42,6 +42,56 @@ __global__ __launch_bounds__(kBlock) void copy_f32_kernel(const float* __restric
     for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// ---- sgap_validate_csr ------------------------------------------------------
+
+static __device__ __align__(256) unsigned long long g_validate_counters[4];
+
+__global__ __launch_bounds__(kBlock) void validate_rowptr_kernel(const int32_t* __restrict__ rowptr, int64_t M,
+                                                                 int64_t nnz, unsigned long long* __restrict__ counters)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    unsigned long long bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < M; i += stride)
+        if (rowptr[i] > rowptr[i + 1]) ++bad;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (rowptr[0] != 0) ++bad;
+        if (rowptr[M] != nnz) ++bad;
+    }
+    if (bad) atomicAdd(&counters[0], bad);
+}
+
+__global__ __launch_bounds__(kBlock) void validate_columns_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                                  int64_t K, unsigned long long* __restrict__ counters)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    unsigned long long bad = 0;
+    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += stride)
+        if (colidx[p] < 0 || colidx[p] >= K) ++bad;
+    if (bad) atomicAdd(&counters[1], bad);
+}
+
+// only for a rowptr that validate_rowptr_kernel found sound: every range then lies inside colidx
+__global__ __launch_bounds__(kBlock) void validate_rows_kernel(const int32_t* __restrict__ rowptr,
+                                                               const int32_t* __restrict__ colidx, int64_t M,
+                                                               unsigned long long* __restrict__ counters)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    unsigned long long unsorted = 0, empty = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < M; i += stride) {
+        const int32_t b = rowptr[i], e = rowptr[i + 1];
+        if (b == e) ++empty;
+        for (int32_t p = b + 1; p < e; ++p)
+            if (colidx[p] <= colidx[p - 1]) ++unsorted;
+    }
+    if (unsorted) atomicAdd(&counters[2], unsorted);
+    if (empty) atomicAdd(&counters[3], empty);
+}
+
+__global__ void validate_reset_kernel(unsigned long long* counters)
+{
+    if (threadIdx.x < 4) counters[threadIdx.x] = 0;
+}
+
 namespace {
 struct LaunchDebugReduce {
     const float* in;
@@ -570,6 +620,45 @@ int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_l
         sgap::plan_nnz_serial(group_size, lanes_per_row, cols_per_lane, nnz_hint, compute_units_, forced_tile);
     *tile = p.tile;
     *merge_on_chip = p.merge ? 1 : 0;
+    return SGAP_OK;
+}
+
+int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, int64_t nnz, int64_t* report,
+                      void* stream)
+{
+    using namespace sgap;
+    if (M < 0 || K < 0 || nnz < 0) return fail(SGAP_ERR_INVALID_ARG, "negative size");
+    if (M > 2147483646LL || nnz > 2147483647LL) return fail(SGAP_ERR_INVALID_ARG, "size exceeds int32 index range");
+    if (!report) return fail(SGAP_ERR_INVALID_ARG, "report must not be null");
+    if (!rowptr) return fail(SGAP_ERR_INVALID_ARG, "rowptr must not be null");
+    if (nnz > 0 && !colidx) return fail(SGAP_ERR_INVALID_ARG, "colidx must not be null when nnz > 0");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // this GPU's copy of the counters (the symbol's name is a host-side stand-in, not a device address)
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_validate_counters)) != hipSuccess)
+        return fail(SGAP_ERR_HIP, "could not locate the counters");
+    unsigned long long* counters = static_cast<unsigned long long*>(sym);
+    const unsigned grid = (unsigned)(compute_units() * 8);
+    unsigned long long host[4] = {0, 0, 0, 0};
+    hipLaunchKernelGGL(validate_reset_kernel, dim3(1), dim3(kWave), 0, s, counters);
+    hipLaunchKernelGGL(validate_rowptr_kernel, dim3(grid), dim3(kBlock), 0, s, rowptr, M, nnz, counters);
+    if (nnz > 0) hipLaunchKernelGGL(validate_columns_kernel, dim3(grid), dim3(kBlock), 0, s, colidx, nnz, K, counters);
+    hipError_t err = hipGetLastError();
+    if (err == hipSuccess) err = hipMemcpyAsync(host, counters, sizeof(host), hipMemcpyDeviceToHost, s);
+    if (err == hipSuccess) err = hipStreamSynchronize(s);
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP error: %s", hipGetErrorString(err));
+    report[0] = (int64_t)host[0];
+    report[1] = (int64_t)host[1];
+    report[2] = report[3] = -1;
+    if (host[0] == 0) {
+        hipLaunchKernelGGL(validate_rows_kernel, dim3(grid), dim3(kBlock), 0, s, rowptr, colidx, M, counters);
+        err = hipGetLastError();
+        if (err == hipSuccess) err = hipMemcpyAsync(host, counters, sizeof(host), hipMemcpyDeviceToHost, s);
+        if (err == hipSuccess) err = hipStreamSynchronize(s);
+        if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP error: %s", hipGetErrorString(err));
+        report[2] = (int64_t)host[2];
+        report[3] = (int64_t)host[3];
+    }
     return SGAP_OK;
 }
 

@@ -130,6 +130,17 @@ def test_tensor_arguments_are_checked_without_launch():
     assert lib.sgap_ttm_csf(0, 4, 4, None, None, None, None, None, 8, 0, 0, -1, None) == 0
 
 
+def test_validate_arguments_are_checked_without_launch():
+    lib = binding.load()
+    report = (ctypes.c_int64 * 4)()
+    assert lib.sgap_validate_csr(-1, 4, 0x1000, 0x2000, 3, report, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_validate_csr(4, 4, 0x1000, 0x2000, -3, report, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_validate_csr(4, 4, None, 0x2000, 3, report, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_validate_csr(4, 4, 0x1000, None, 3, report, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_validate_csr(4, 4, 0x1000, 0x2000, 3, None, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"null" in lib.sgap_last_error()
+
+
 def test_empty_shapes_are_ok_without_launch():
     lib = binding.load()
     assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0

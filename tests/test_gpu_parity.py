@@ -433,3 +433,36 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         torch.cuda.synchronize()
         for C, pt in zip(outs, points):
             assert_close(C, C_ref, BND, exact=True, what=f"graph replay {replay} {ids(pt)}")
+
+
+def test_validate_csr_counts_what_is_wrong():
+    p = wl.make_problem("powerlaw", scale_down=8)
+    rp = torch.from_numpy(p.rowptr).cuda()
+    ci = torch.from_numpy(p.colidx).cuda()
+    empty = int((np.diff(p.rowptr) == 0).sum())
+    assert binding.sgap_validate_csr(p.M, p.K, rp, ci) == (0, 0, 0, empty)
+    # columns out of range, on either side
+    bad = ci.clone()
+    bad[5] = -1
+    bad[77] = p.K
+    bad[78] = p.K + 5
+    assert binding.sgap_validate_csr(p.M, p.K, rp, bad)[:2] == (0, 3)
+    # a row whose columns are not ascending, and a repeated column
+    long_row = int(np.argmax(np.diff(p.rowptr)))
+    a = int(p.rowptr[long_row])
+    uns = ci.clone()
+    uns[a], uns[a + 1] = ci[a + 1].item(), ci[a].item()
+    uns[a + 3] = uns[a + 2]
+    assert binding.sgap_validate_csr(p.M, p.K, rp, uns) == (0, 0, 2, empty)
+    # a damaged rowptr: one decreasing pair, a first entry that is not 0, a last entry that is not nnz
+    rbad = rp.clone()
+    rbad[10] = rbad[11] + 1
+    assert binding.sgap_validate_csr(p.M, p.K, rbad, ci) == (2 if rbad[9] > rbad[10] else 1, 0, -1, -1)
+    rbad = rp.clone()
+    rbad[0] = 1 if p.rowptr[1] >= 1 else 0
+    rbad[-1] += 1
+    got = binding.sgap_validate_csr(p.M, p.K, rbad, ci)
+    assert got[0] == (2 if p.rowptr[1] >= 1 else 1) and got[2:] == (-1, -1)
+    # an empty matrix is fine
+    z = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+    assert binding.sgap_validate_csr(7, 5, z, torch.zeros(0, dtype=torch.int32, device="cuda:0")) == (0, 0, 0, 7)
