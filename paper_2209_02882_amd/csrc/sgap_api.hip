@@ -415,9 +415,10 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* f
     const bool par = strategy == SGAP_REDUCE_PARALLEL;
     const int g = par ? group_size : 1;
     const int lc = pow2_ceil_capped((J + vec - 1) / vec, 64 / g);
-    // parallel: a group takes one slice at a time (two where groups are wide and a
-    // workgroup would otherwise hold only a few slices); serial: group_size slices per lane
-    const int rows_per_slot = !par ? group_size : g_rows_per_slot > 0 ? g_rows_per_slot : (g * lc >= 64 ? 2 : 1);
+    // parallel: about 16 slices per workgroup, enough to pay for bringing a block's slice pointers,
+    // fibers and entries into LDS (more lose occupancy to the LDS copies); serial: group_size slices per lane
+    const int slots = 256 / (g * lc);
+    const int rows_per_slot = !par ? group_size : g_rows_per_slot > 0 ? g_rows_per_slot : (slots >= 16 ? 1 : 16 / slots);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     auto mark = [&](hipEvent_t& ev) {
