@@ -15,7 +15,11 @@
  * Conventions for every entry point
  *   - All array arguments are DEVICE pointers owned by the caller.  The
  *     library reads rowptr/colidx/vals/B, overwrites C, keeps no pointer
- *     after the call returns and allocates no device memory.
+ *     after the call returns and allocates no device memory.  (Two paths
+ *     keep working data in file-scope device arrays of the library, one copy
+ *     per GPU: the long-rows-by-windows path, see SGAP_TUNE_LONG_ROW_MIN, and
+ *     sgap_validate_csr.  Calls that use one of them must not overlap on one
+ *     GPU; all other calls may run concurrently on different streams.)
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and the call returns without waiting.
  *   - A call only enqueues kernels (no allocation, no host synchronisation, no
@@ -299,7 +303,9 @@ int sgap_version(void);
  *   SGAP_TUNE_ROWS_PER_GROUP  rows one group works through per
  *                        work item in the row-split parallel strategy (the
  *                        serial strategy takes group_size rows by definition);
- *                        0 = automatic, from the mean row length.
+ *                        0 = automatic, from the mean row length.  Also the
+ *                        slices per group of sgap_mttkrp_csf's parallel strategy
+ *                        (automatic: about 16 slices per workgroup).
  *   SGAP_TUNE_PERSISTENT 1: the row-split schedule launches only as many
  *                        workgroups as the chip holds at once and each loops
  *                        over work items; 0 (default): one workgroup per item.
