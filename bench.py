@@ -195,6 +195,8 @@ def main_sddmm(a):
     X1h = wl.sddmm_left_operand(p)
     log(f"[bench] sddmm on {a.workload}: {p.row_stats()}")
     dp = DeviceProblem(p)
+    binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, a.long_row_min)
+    binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, a.window_kb)
     X1 = torch.from_numpy(X1h).cuda()
     out_vals = torch.empty(p.nnz, dtype=torch.float32, device="cuda:0")
     min_bytes = wl.sddmm_minimal_bytes(p)
@@ -252,7 +254,7 @@ def main_sddmm(a):
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": a.workload, "op": "sddmm", "M": p.M, "K": p.K, "J": p.N, "nnz": p.nnz,
-                   "group_size": g, "strategy": st},
+                   "group_size": g, "strategy": st, "long_row_min": a.long_row_min},
         "copy_kernel_gbs": copy_gbs,
         "roofline": {
             "bound": "hbm",
@@ -260,7 +262,8 @@ def main_sddmm(a):
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st)) if a.ncols is None else None,
+            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st) + ((a.long_row_min,) if a.long_row_min else ()))
+            if a.ncols is None and not a.window_kb else None,
             "kernel_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },

@@ -335,6 +335,11 @@ int sgap_version(void);
  *                        device array of the library, about 8.4 MB per GPU,
  *                        shared by all calls on that GPU: calls that use it
  *                        must not overlap on one GPU.  0 (default) = off.
+ *                        sgap_sddmm_csr takes the same path for the stored
+ *                        entries of such rows when J % 4 == 0, 32 <= J <= 256
+ *                        and X1, X2T are 16-byte aligned (no atomics there:
+ *                        every entry still has one writer); all other entries
+ *                        then go through the kernel without the row cache.
  *   SGAP_TUNE_PANEL_WINDOW_KB  KiB of B per column window of that path (at most
  *                        255 windows are made); 0 = automatic (2048).
  */

@@ -373,8 +373,14 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     };
     mark(ev0);
     const bool par = strategy == SGAP_REDUCE_PARALLEL;
-    hipError_t err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, g_sddmm_row_cache != 0, compute_units(),
-                                  nnz_hint, s);
+    hipError_t err;
+    if (g_long_row_min > 0 && vec == 4 && J >= 32 && J <= 256)
+        err = launch_sddmm_panels(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size,
+                                  g_xcd_remap == 0 ? 1 : kXcds, compute_units(), nnz_hint, g_long_row_min,
+                                  (int64_t)(g_panel_window_kb > 0 ? g_panel_window_kb : 2048) * 1024, s);
+    else
+        err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, g_sddmm_row_cache != 0,
+                           compute_units(), nnz_hint, s);
     if (ev0) {
         mark(ev1);
         if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);

@@ -22,6 +22,15 @@ struct SpmmArgs {
     int group;        // group_size
 };
 
+// Rows another kernel produces: when *count <= max_rows, rows of at least
+// min_len stored entries are neither computed nor written by the kernel that
+// is handed this.  count = nullptr: no row is left out.
+struct RowSkip {
+    const uint32_t* __restrict__ count;
+    uint32_t max_rows;
+    int32_t min_len;
+};
+
 // How the (row block x column tile) work items of a row-split launch are
 // laid over the grid.  The 8 accelerator dies (XCDs) of the chip each have a
 // private L2 and receive workgroups round-robin (workgroup b runs on XCD
@@ -189,6 +198,15 @@ hipError_t launch_debug_group_reduce(const float* in, float* out, int g, int r, 
 // row_cache lets the parallel strategy keep rows of X1 in registers where the shape allows.
 hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int vec, bool row_cache,
                         int compute_units, int64_t nnz_hint, hipStream_t stream);
+// the same with the stored entries of rows of at least min_len entries produced
+// window by window of X2T (sgap_panels.hip) and all others by the plain kernel;
+// vec must be 4 and 32 <= J <= 256
+hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int xcds,
+                               int compute_units, int64_t nnz_hint, int32_t min_len, int64_t window_bytes,
+                               hipStream_t stream);
+// the plain SDDMM kernel (no row cache) that leaves the entries of the rows described by `skip` alone
+hipError_t launch_sddmm_skip(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int compute_units,
+                             int64_t nnz_hint, const RowSkip& skip, hipStream_t stream);
 // MTTKRP on compressed sparse fibers: g lanes per slice (1 for the serial
 // strategy), rows_per_slot slices per group (consecutive, or interleaved with
 // the other groups' slices), lc chunk lanes of vec columns each.

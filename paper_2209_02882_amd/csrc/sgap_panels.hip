@@ -79,10 +79,10 @@ __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, Pan
     }
 }
 
-// Window pointers of the long rows, and zeros in their rows of C.
+// Window pointers of the long rows, and (zero_rows) zeros in their rows of C.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelScratch* scr, int windows,
-                                                                int32_t window_rows)
+                                                                int32_t window_rows, int zero_rows)
 {
     const uint32_t n = scr->count;
     if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
@@ -108,6 +108,7 @@ __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, Pane
         }
         scr->ptr[(int64_t)i * per_row + w] = lo;
     }
+    if (!zero_rows) return;
     const int64_t chunks = a.N / VEC;  // N % VEC == 0
     Vec<VEC> z;
     z.zero();
@@ -269,6 +270,24 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
     *window_rows = (int32_t)rows;
 }
 
+// The preparation both operators share: list of the rows of at least min_len
+// entries, their window pointers, and (zero_rows) zeros in their rows of C.
+hipError_t launch_panel_preparation(const SpmmArgs& a, int32_t min_len, int64_t window_bytes, bool zero_rows,
+                                    int compute_units, hipStream_t s, PanelScratch** scratch, int* windows)
+{
+    PanelScratch* scr = panel_scratch();
+    if (!scr) return hipErrorInvalidValue;
+    int32_t window_rows = 1;
+    plan_panels(a.K, a.N, window_bytes, windows, &window_rows);
+    hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
+    hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
+                       min_len);
+    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, *windows,
+                       window_rows, zero_rows ? 1 : 0);
+    *scratch = scr;
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // Long rows (at least min_len entries) window by window, all other rows by the
@@ -279,17 +298,10 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
                                    int64_t window_bytes, hipStream_t s)
 {
     if (vec != 4 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
-    PanelScratch* scr = panel_scratch();
-    if (!scr) return hipErrorInvalidValue;
+    PanelScratch* scr = nullptr;
     int windows = 1;
-    int32_t window_rows = 1;
-    plan_panels(a.K, a.N, window_bytes, &windows, &window_rows);
-
-    hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
-    hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
-                       min_len);
-    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, windows,
-                       window_rows);
+    hipError_t err = launch_panel_preparation(a, min_len, window_bytes, true, compute_units, s, &scr, &windows);
+    if (err != hipSuccess) return err;
     // one wavefront per item: chunk lanes for the columns of one pass, the rest of the 64 lanes split the entries
     int wave_lc = 1;
     while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
@@ -302,7 +314,7 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
         case 32: launch_long_rows<2, 32, 4>(a, scr, windows, xcds, compute_units, s); break;
         default: launch_long_rows<1, 64, 4>(a, scr, windows, xcds, compute_units, s); break;
     }
-    hipError_t err = hipGetLastError();
+    err = hipGetLastError();
     if (err != hipSuccess) return err;
 
     row_split_detail::Launch<false, true> f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units,
@@ -310,6 +322,177 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
                                             RowSkip{&scr->count, (uint32_t)kPanelMaxRows, min_len}};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
+}
+
+// ---- SDDMM ------------------------------------------------------------------
+
+// One SDDMM item: out[p] = vals[p] * <X1[row, :], X2T[colidx[p], :]> for the
+// entries [p0, p1) of a long row, by one wavefront of G members x LC chunk lanes
+// (LC >= 8, J <= LC*4: a lane owns four columns).  The members split the entries
+// eight at a time; a member's LC lanes hold partial dot products of its eight
+// entries and sum them in log2(LC) exchange steps, the first three of which halve
+// the number of values a lane carries (8, 4, 2, 1), so that the eight sums cost
+// ten exchanges instead of 8 * log2(LC).  Afterwards lane c of a member holds the
+// sum of entry c >> (log2(LC) - 3), and the lanes whose low bits are zero write.
+template <int G, int LC>
+__device__ __forceinline__ void panel_sddmm_item(const SpmmArgs& a, const float* __restrict__ X1,
+                                                 float* __restrict__ out, int32_t p0, int32_t p1, int64_t row, int lane)
+{
+    constexpr int VEC = 4;
+    constexpr int V = 8;  // entries per member and batch
+    static_assert(LC >= 8 && G * LC == kWave, "eight values are halved three times");
+    const int member = lane / LC;
+    const int chunk = lane % LC;
+    const int64_t J = a.N;
+    const int64_t k = (int64_t)chunk * VEC;
+    const bool k_ok = k < J;
+    Vec<VEC> x1;
+    x1.zero();
+    if (k_ok) x1 = load_vec<VEC>(X1 + row * J + k);
+    for (int32_t base = p0; base < p1; base += kWave) {
+        int32_t my_col = 0, my_val = 0;
+        if (base + lane < p1) {
+            my_col = load_stream(a.colidx + base + lane);
+            my_val = __float_as_int(load_stream(a.vals + base + lane));
+        }
+        const int cnt = p1 - base < kWave ? p1 - base : kWave;
+        for (int j0 = 0; j0 < cnt; j0 += G * V) {
+            // member m takes entries j0 + u*G + m, u < 8
+            int32_t col[V];
+            float val[V], part[V];
+            Vec<VEC> x2[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const int j = j0 + u * G + member;
+                col[u] = __shfl(my_col, j & (kWave - 1), kWave);
+                val[u] = __int_as_float(__shfl(my_val, j & (kWave - 1), kWave));
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                x2[u].zero();
+                if (k_ok && j0 + u * G + member < cnt) x2[u] = load_vec<VEC>(a.B + (int64_t)col[u] * J + k);
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                part[u] = 0.0f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) part[u] = __builtin_fmaf(x1.v[v], x2[u].v[v], part[u]);
+            }
+            // 8 -> 4 -> 2 -> 1 values: the upper half of each pair of lane halves keeps the upper half of the values
+            float four[4], two[2], one;
+            {
+                const bool up = (chunk & (LC / 2)) != 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float keep = up ? part[u + 4] : part[u];
+                    const float send = up ? part[u] : part[u + 4];
+                    four[u] = keep + __shfl_xor(send, LC / 2, LC);
+                }
+            }
+            {
+                const bool up = (chunk & (LC / 4)) != 0;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const float keep = up ? four[u + 2] : four[u];
+                    const float send = up ? four[u] : four[u + 2];
+                    two[u] = keep + __shfl_xor(send, LC / 4, LC);
+                }
+            }
+            {
+                const bool up = (chunk & (LC / 8)) != 0;
+                const float keep = up ? two[1] : two[0];
+                const float send = up ? two[0] : two[1];
+                one = keep + __shfl_xor(send, LC / 8, LC);
+            }
+#pragma unroll
+            for (int m = LC / 16; m >= 1; m /= 2) one += __shfl_xor(one, m, LC);
+            // this lane's entry of the batch, and its value
+            const int u_mine = chunk / (LC / 8);
+            float val_mine = val[0];
+#pragma unroll
+            for (int u = 1; u < V; ++u)
+                if (u == u_mine) val_mine = val[u];
+            const int j = j0 + u_mine * G + member;
+            if (chunk % (LC / 8) == 0 && j < cnt) out[base + j] = val_mine * one;
+        }
+    }
+}
+
+template <int G, int LC>
+__global__ __launch_bounds__(kBlock) void panel_sddmm_kernel(SpmmArgs a, const float* __restrict__ X1,
+                                                             float* __restrict__ out, PanelScratch* scr, int windows,
+                                                             int xcds)
+{
+    __shared__ uint32_t s_claim;
+    const uint32_t n = scr->count;
+    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const int lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
+    const int per_row = windows + 1;
+    const int xcd = blockIdx.x % xcds;
+    const int64_t my_windows = xcd < windows ? (windows - xcd + xcds - 1) / xcds : 0;
+    const uint32_t items = (uint32_t)(my_windows * n);
+    for (;;) {  // claims as in panel_long_rows_kernel
+        __syncthreads();
+        if (threadIdx.x == 0) s_claim = atomicAdd(&scr->next[xcd], (uint32_t)kPanelClaim);
+        __syncthreads();
+        const uint32_t claim = s_claim;
+        if (claim >= items) break;
+        for (int r = 0; r < kPanelClaim / kWavesPerBlock; ++r) {
+            const uint32_t it = claim + (uint32_t)(r * kWavesPerBlock + wave);
+            if (it >= items) break;
+            const int w = xcd + xcds * (int)(it / n);
+            const int i = (int)(it % n);
+            const int32_t p0 = scr->ptr[(int64_t)i * per_row + w];
+            const int32_t p1 = scr->ptr[(int64_t)i * per_row + w + 1];
+            if (p0 < p1) panel_sddmm_item<G, LC>(a, X1, out, p0, p1, scr->rows[i], lane);
+        }
+    }
+}
+
+namespace {
+
+template <int G, int LC>
+void launch_sddmm_long_rows(const SpmmArgs& a, const float* X1, float* out, PanelScratch* scr, int windows, int xcds,
+                            int compute_units, hipStream_t s)
+{
+    static const int per_cu = [] {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, panel_sddmm_kernel<G, LC>, kBlock, 0) != hipSuccess || n < 1)
+            n = 1;
+        return n;
+    }();
+    int grid = per_cu * compute_units;
+    grid -= grid % xcds;
+    if (grid < xcds) grid = xcds;
+    hipLaunchKernelGGL((panel_sddmm_kernel<G, LC>), dim3(grid), dim3(kBlock), 0, s, a, X1, out, scr, windows, xcds);
+}
+
+}  // namespace
+
+// a: M, K, N = J, rowptr, colidx, vals, B = X2T.  Requires 16-byte loads (J % 4 == 0,
+// aligned X1 and X2T) and 32 <= J <= 256.
+hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int xcds,
+                               int compute_units, int64_t nnz_hint, int32_t min_len, int64_t window_bytes,
+                               hipStream_t s)
+{
+    if (a.N % 4 != 0 || a.N < 32 || a.N > 256 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
+    PanelScratch* scr = nullptr;
+    int windows = 1;
+    hipError_t err = launch_panel_preparation(a, min_len, window_bytes, false, compute_units, s, &scr, &windows);
+    if (err != hipSuccess) return err;
+    int wave_lc = 8;
+    while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
+    switch (wave_lc) {
+        case 8: launch_sddmm_long_rows<8, 8>(a, X1, out, scr, windows, xcds, compute_units, s); break;
+        case 16: launch_sddmm_long_rows<4, 16>(a, X1, out, scr, windows, xcds, compute_units, s); break;
+        case 32: launch_sddmm_long_rows<2, 32>(a, X1, out, scr, windows, xcds, compute_units, s); break;
+        default: launch_sddmm_long_rows<1, 64>(a, X1, out, scr, windows, xcds, compute_units, s); break;
+    }
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    return launch_sddmm_skip(a, X1, out, g, per_lane, compute_units, nnz_hint,
+                             RowSkip{&scr->count, (uint32_t)kPanelMaxRows, min_len}, s);
 }
 
 }  // namespace sgap

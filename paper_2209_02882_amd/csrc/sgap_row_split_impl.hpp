@@ -11,14 +11,6 @@ namespace sgap {
 constexpr int kStageCap = 2048;  // (column, value) pairs per LDS chunk: 16 KB
 constexpr int kRowCap = 1024;    // rowptr entries kept in LDS per row block (+1)
 
-// Rows another kernel produces: when *count <= max_rows, rows of at least
-// min_len stored entries are neither multiplied out nor written here.
-struct RowSkip {
-    const uint32_t* __restrict__ count;
-    uint32_t max_rows;
-    int32_t min_len;
-};
-
 // PARTIAL: the G members of a row reduce in sub-groups of `reduce_members`
 // (a power of two below G) and the first member of every sub-group adds its
 // sum to C with atomics; C must hold zeros before the launch.

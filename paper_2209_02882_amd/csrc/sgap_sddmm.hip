@@ -31,6 +31,7 @@ struct SddmmArgs {
     SpmmArgs a;       // M, K, N = J, rowptr, colidx, vals; B = X2T; C unused
     const float* __restrict__ X1;
     float* __restrict__ out;
+    RowSkip skip;     // entries of these rows are left alone (kernels instantiated with SKIP only)
 };
 
 template <int VEC>
@@ -45,9 +46,12 @@ __device__ __forceinline__ float dot_vec(const Vec<VEC>& x, const Vec<VEC>& y, f
 // entry through the rowptr window (cut at row boundaries where long runs of
 // empty rows overflow it).  row_lb = a row at or before the tile's first
 // entry.  Block-uniform; the LDS arrays are ready on return.
+// skip_len > 0: entries of rows of at least skip_len stored entries get the
+// one's complement of their row (a negative number) instead.
 __device__ __forceinline__ void stage_tile(const SpmmArgs& a, int32_t tile_start, int32_t tile_end, int32_t row_lb,
                                            int32_t* __restrict__ s_col, float* __restrict__ s_val,
-                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_win)
+                                           int32_t* __restrict__ s_row, int32_t* __restrict__ s_win,
+                                           int32_t skip_len = 0)
 {
     const int tid = threadIdx.x;
     const int cnt = tile_end - tile_start;
@@ -59,8 +63,11 @@ __device__ __forceinline__ void stage_tile(const SpmmArgs& a, int32_t tile_start
     for (int32_t base = tile_start; base < tile_end;) {
         __syncthreads();
         const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
-        for (int i = tid; i < w.cnt; i += kBlock)
-            s_row[base - tile_start + i] = row_lb + last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
+        for (int i = tid; i < w.cnt; i += kBlock) {
+            const int32_t wi = last_row_at_or_before(s_win, w.n_first, w.n_last, base + i);
+            const bool skipped = skip_len > 0 && s_win[wi + 1] - s_win[wi] >= skip_len;
+            s_row[base - tile_start + i] = skipped ? ~(row_lb + wi) : row_lb + wi;
+        }
         row_lb += w.n_last;
         base += w.cnt;
     }
@@ -69,7 +76,8 @@ __device__ __forceinline__ void stage_tile(const SpmmArgs& a, int32_t tile_start
 
 // per_lane = 0: parallel strategy, G lanes per entry.  per_lane > 0 (G = 1):
 // serial strategy, per_lane consecutive entries per lane.
-template <int G, int VEC>
+// SKIP: leave the entries of the rows described by s.skip alone.
+template <int G, int VEC, bool SKIP = false>
 __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane)
 {
     __shared__ int32_t s_col[kSddmmTile];
@@ -90,6 +98,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
     const TileDeal deal(tiles, blockIdx.x, gridDim.x);
     const int64_t my_tiles = deal.mine;
     if (my_tiles == 0) return;
+    int32_t skip_len = 0;
+    if constexpr (SKIP) skip_len = *s.skip.count <= s.skip.max_rows ? s.skip.min_len : 0;
 
     for (int64_t j0 = 0; j0 < my_tiles; j0 += kTileRowBatch) {
         find_tile_rows(a, deal, j0, kSddmmTile, s_tile_row);
@@ -101,7 +111,14 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
             const int cnt = tile_end - tile_start;
             const int32_t row_lb = s_tile_row[j - j0];
 
-            stage_tile(a, tile_start, tile_end, row_lb, s_col, s_val, s_row, s_win);
+            if constexpr (SKIP) {
+                // a tile that lies inside one skipped row is not even staged (row_lb is the row of the tile's
+                // first entry; the same two words for every lane, so the workgroup stays together)
+                if (skip_len > 0 && a.rowptr[row_lb + 1] >= tile_end &&
+                    a.rowptr[row_lb + 1] - a.rowptr[row_lb] >= skip_len)
+                    continue;
+            }
+            stage_tile(a, tile_start, tile_end, row_lb, s_col, s_val, s_row, s_win, skip_len);
 
             if (per_lane == 0) {
                 // U entries per group at a time, so that 2*U rows are in flight
@@ -115,6 +132,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
                     for (int u = 0; u < U; ++u) {
                         const int e = e0 + u * SLOTS + slot;
                         ok[u] = e < cnt;
+                        if constexpr (SKIP) ok[u] = ok[u] && s_row[e] >= 0;
                         const int32_t row = ok[u] ? s_row[e] : 0;
                         const int32_t col = ok[u] ? s_col[e] : 0;
                         x1p[u] = s.X1 + (int64_t)row * J;
@@ -148,6 +166,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(SddmmArgs s, int per_lane
                 constexpr int U = kSddmmDepth;
                 for (int i = 0; i < per_lane; ++i) {
                     for (int e = (tid * per_lane + i); e < cnt; e += kBlock * per_lane) {
+                        if constexpr (SKIP) {
+                            if (s_row[e] < 0) continue;
+                        }
                         const float* __restrict__ x1p = s.X1 + (int64_t)s_row[e] * J;
                         const float* __restrict__ x2p = X2T + (int64_t)s_col[e] * J;
                         float acc = 0.0f;
@@ -305,6 +326,14 @@ void launch_one(const SddmmArgs& s, int per_lane, int compute_units, int64_t nnz
 }
 
 template <int G>
+void launch_skip(const SddmmArgs& s, int per_lane, int compute_units, int64_t nnz_hint, hipStream_t stream)
+{
+    static const int per_cu = resident_per_cu(sddmm_kernel<G, 4, true>, 0);
+    const int grid = persistent_grid(per_cu, compute_units, nnz_hint, kSddmmTile);
+    hipLaunchKernelGGL((sddmm_kernel<G, 4, true>), dim3(grid), dim3(kBlock), 0, stream, s, per_lane);
+}
+
+template <int G>
 bool launch_vec(const SddmmArgs& s, int vec, int per_lane, int compute_units, int64_t nnz_hint, hipStream_t stream)
 {
     switch (vec) {
@@ -330,6 +359,7 @@ hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, i
     s.a = a;
     s.X1 = X1;
     s.out = out;
+    s.skip = RowSkip{nullptr, 0, 0};
     bool ok = false;
     if (per_lane > 0) {
         ok = launch_vec<1>(s, vec, per_lane, compute_units, nnz_hint, stream);
@@ -358,6 +388,29 @@ hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, i
         }
     }
     if (!ok) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// The plain kernel (16-byte loads: J % 4 == 0, aligned operands) with the
+// entries of the rows described by `skip` left alone.
+hipError_t launch_sddmm_skip(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int compute_units,
+                             int64_t nnz_hint, const RowSkip& skip, hipStream_t stream)
+{
+    SddmmArgs s;
+    s.a = a;
+    s.X1 = X1;
+    s.out = out;
+    s.skip = skip;
+    switch (per_lane > 0 ? 1 : g) {
+        case 1: launch_skip<1>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 2: launch_skip<2>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 4: launch_skip<4>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 8: launch_skip<8>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 16: launch_skip<16>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 32: launch_skip<32>(s, per_lane, compute_units, nnz_hint, stream); break;
+        case 64: launch_skip<64>(s, per_lane, compute_units, nnz_hint, stream); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -179,3 +179,73 @@ def test_wide_matrix_offsets_need_64_bits(panels):
                                  binding.SCHEDULES[point[2]])
         torch.cuda.synchronize()
         assert_close(C, C_ref, BND, exact=True, what=f"64-bit offsets {point}")
+
+
+# ---------------------------------------------------------------- SDDMM on the same path
+
+SDDMM_POINTS = [(g, st) for st in ("parallel", "serial") for g in binding.GROUP_SIZES]
+
+
+def sddmm_reference(p, X1):
+    return oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=8)
+
+
+def check_sddmm(dp, X1d, ref, bnd, exact, what, points=SDDMM_POINTS):
+    for g, st in points:
+        got = dp.run_sddmm(X1d, g, st).cpu().numpy().astype(np.float64)
+        assert not np.isnan(got).any(), f"{what} g={g} {st}: entries left unwritten"
+        if exact:
+            assert np.array_equal(got, ref), f"{what} g={g} {st}: {np.count_nonzero(got != ref)} entries differ"
+        else:
+            bad = np.abs(got - ref) > TOL * bnd
+            assert not bad.any(), f"{what} g={g} {st}: {bad.sum()} entries outside tolerance"
+
+
+@pytest.mark.parametrize("J", [32, 36, 64, 100, 128, 256, 16, 260])
+def test_sddmm_long_rows_by_windows_match_the_oracle(panels, J):
+    # J = 16 and 260 lie outside the path's range: the plain kernels must run as if the knob were off
+    M, K = 1200, 5000
+    p = csr_problem("mixed", M, K, J, mixed_lengths(M, K, J + 1), seed=J + 1, integer=True)
+    X1 = wl.fill_values(np.random.default_rng(J), M * J, True).reshape(M, J)
+    ref, bnd = sddmm_reference(p, X1)
+    dp = DeviceProblem(p)
+    X1d = torch.from_numpy(X1).cuda()
+    for window_kb in (0, 64, 1):
+        panels(100, window_kb)
+        check_sddmm(dp, X1d, ref, bnd, True, f"J={J} window {window_kb} KiB")
+
+
+def test_sddmm_window_path_float_values_and_edges(panels):
+    M, K, J = 2500, 30000, 128
+    p = csr_problem("mixed", M, K, J, mixed_lengths(M, K, 17, long_len=(900, 7000)), seed=17)
+    X1 = wl.fill_values(np.random.default_rng(18), M * J, False).reshape(M, J)
+    ref, bnd = sddmm_reference(p, X1)
+    dp = DeviceProblem(p)
+    X1d = torch.from_numpy(X1).cuda()
+    for min_len in (900, 1, 100000):  # some rows, every non-empty row, no row
+        panels(min_len, 512)
+        check_sddmm(dp, X1d, ref, bnd, False, f"min_len={min_len}", points=[(8, "parallel"), (1, "parallel"), (4, "serial")])
+    # more long rows than the list holds: the path switches itself off
+    M2 = 9000
+    p2 = csr_problem("many_long", M2, 300, 32, np.full(M2, 5), seed=19, integer=True)
+    X12 = wl.fill_values(np.random.default_rng(20), M2 * 32, True).reshape(M2, 32)
+    ref2, bnd2 = sddmm_reference(p2, X12)
+    panels(2, 4)
+    check_sddmm(DeviceProblem(p2), torch.from_numpy(X12).cuda(), ref2, bnd2, True, "overflow",
+                points=[(4, "parallel"), (8, "serial")])
+
+
+def test_sddmm_full_size_skewed_every_entry(panels):
+    p = wl.make_problem("skewed")
+    X1 = wl.sddmm_left_operand(p)
+    ref, bnd = oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=16)
+    dp = DeviceProblem(p)
+    X1d = torch.from_numpy(X1).cuda()
+    ref_t, bnd_t = torch.from_numpy(ref).cuda(), torch.from_numpy(bnd).cuda()
+    panels(1024)
+    for g, st in [(8, "parallel"), (16, "parallel"), (4, "serial")]:
+        print("  sddmm point", g, st, flush=True)
+        out = dp.run_sddmm(X1d, g, st)
+        assert not torch.isnan(out).any(), f"g={g} {st}: entry never written"
+        bad = (out.double() - ref_t).abs() > TOL * bnd_t
+        assert not bool(bad.any()), f"g={g} {st}: {int(bad.sum())} entries out of tolerance"
