@@ -119,6 +119,16 @@ __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, Pane
     }
 }
 
+// Value that lane `j` of the wavefront holds.  With one member per wavefront
+// (UNIFORM) every lane asks for the same j, and the value comes back in a
+// scalar register, so that the address arithmetic on it runs on the scalar unit.
+template <bool UNIFORM>
+__device__ __forceinline__ int32_t from_lane(int32_t v, int j)
+{
+    if constexpr (UNIFORM) return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(j));
+    else return __shfl(v, j, kWave);
+}
+
 constexpr int kPanelDepth = 8;   // gathered rows of B in flight per lane
 constexpr int kPanelClaim = 16;  // items a workgroup takes from its die's counter at a time
 
@@ -154,8 +164,8 @@ __device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_
 #pragma unroll
                 for (int u = 0; u < D; ++u) {
                     const int j = j0 + u * G + member;
-                    col[u] = __shfl(my_col, j & (kWave - 1), kWave);
-                    val[u] = __int_as_float(__shfl(my_val, j & (kWave - 1), kWave));
+                    col[u] = from_lane<G == 1>(my_col, j & (kWave - 1));
+                    val[u] = __int_as_float(from_lane<G == 1>(my_val, j & (kWave - 1)));
                     if (j >= cnt) val[u] = 0.0f;
                 }
 #pragma unroll
@@ -364,8 +374,8 @@ __device__ __forceinline__ void panel_sddmm_item(const SpmmArgs& a, const float*
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 const int j = j0 + u * G + member;
-                col[u] = __shfl(my_col, j & (kWave - 1), kWave);
-                val[u] = __int_as_float(__shfl(my_val, j & (kWave - 1), kWave));
+                col[u] = from_lane<G == 1>(my_col, j & (kWave - 1));
+                val[u] = __int_as_float(from_lane<G == 1>(my_val, j & (kWave - 1)));
             }
 #pragma unroll
             for (int u = 0; u < V; ++u) {
