@@ -131,18 +131,22 @@ __device__ __forceinline__ int32_t from_lane(int32_t v, int j)
 
 constexpr int kPanelDepth = 8;   // gathered rows of B in flight per lane
 constexpr int kPanelClaim = 16;  // items a workgroup takes from its die's counter at a time
+// Chunk lanes per column tile of the SpMM path: 64 lanes = 256 columns, the widest a wavefront covers.
+// Narrower tiles would let a window hold more rows and so need fewer atomic pieces per row of C, but
+// the narrower gathers cost more than that saves (skewed: 3.46 ms at 64 lanes, 3.69 at 32, 4.11 at 16).
+constexpr int kPanelTileLanes = 64;
 
-// One item: the entries [p0, p1) of row `row`, multiplied out by one wavefront
-// whose 64 lanes are G members x LC chunk lanes: the members split the entries,
-// the group tree-sums and member 0 adds the partial row into C.  p0, p1 and row
-// are the same in all lanes.
+// One item: the entries [p0, p1) of row `row` times the columns k0 .. k0 + LC*VEC
+// of B, multiplied out by one wavefront whose 64 lanes are G members x LC chunk
+// lanes: the members split the entries, the group tree-sums and member 0 adds
+// the partial row into C.  p0, p1, row and k0 are the same in all lanes.
 template <int G, int LC, int VEC, bool OFF32>
-__device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_t p1, int64_t row, int lane)
+__device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_t p1, int64_t row, int64_t k0, int lane)
 {
     constexpr int D = kPanelDepth;
     const int member = lane / LC;
     const int chunk = lane % LC;
-    for (int64_t k0 = 0; k0 < a.N; k0 += (int64_t)LC * VEC) {
+    {
         const int64_t k = k0 + (int64_t)chunk * VEC;
         const bool k_ok = k < a.N;
         const BRow<OFF32> brow(a.B, a.N, k_ok ? k : 0);
@@ -200,10 +204,12 @@ __device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_
     }
 }
 
-// Die x takes the windows x, x + xcds, ...; its items, window-major, are handed
-// out to its workgroups kPanelClaim at a time from one counter, one item per
+// B is cut into blocks of one window of rows by one tile of LC*VEC columns
+// (one tile unless N > 256), about 2 MiB each.  Die x takes the blocks x,
+// x + xcds, ... (window-major); its items (block, long row) are handed out to
+// its workgroups kPanelClaim at a time from one counter, one item per
 // wavefront.  Items differ in length by a factor of ten and more: with a fixed
-// deal the wavefronts of a die drift more than a window apart, which the L2
+// deal the wavefronts of a die drift more than a block apart, which the L2
 // cannot hold (43 GB fetched instead of 1.8 GB on the skewed workload), and one
 // item per claim makes the counter the bottleneck (a returning atomic on one
 // address takes about 0.1 us).
@@ -218,8 +224,10 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
     const int wave = threadIdx.x / kWave;
     const int per_row = windows + 1;
     const int xcd = blockIdx.x % xcds;
-    const int64_t my_windows = xcd < windows ? (windows - xcd + xcds - 1) / xcds : 0;
-    const uint32_t items = (uint32_t)(my_windows * n);  // at most 255 * 8192
+    const int tiles = (int)((a.N + LC * VEC - 1) / (LC * VEC));
+    const int64_t blocks = (int64_t)windows * tiles;
+    const int64_t my_blocks = xcd < blocks ? (blocks - xcd + xcds - 1) / xcds : 0;
+    const uint32_t items = (uint32_t)(my_blocks * n);  // host: blocks * kPanelMaxRows < 2^32
     for (;;) {
         __syncthreads();  // everyone has read the previous claim
         if (threadIdx.x == 0) s_claim = atomicAdd(&scr->next[xcd], (uint32_t)kPanelClaim);
@@ -229,11 +237,13 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
         for (int r = 0; r < kPanelClaim / kWavesPerBlock; ++r) {
             const uint32_t it = claim + (uint32_t)(r * kWavesPerBlock + wave);
             if (it >= items) break;
-            const int w = xcd + xcds * (int)(it / n);
+            const int64_t block = xcd + (int64_t)xcds * (it / n);
+            const int w = (int)(block / tiles);
+            const int64_t k0 = (block % tiles) * (LC * VEC);
             const int i = (int)(it % n);
             const int32_t p0 = scr->ptr[(int64_t)i * per_row + w];
             const int32_t p1 = scr->ptr[(int64_t)i * per_row + w + 1];
-            if (p0 < p1) panel_item<G, LC, VEC, OFF32>(a, p0, p1, scr->rows[i], lane);
+            if (p0 < p1) panel_item<G, LC, VEC, OFF32>(a, p0, p1, scr->rows[i], k0, lane);
         }
     }
 }
@@ -282,13 +292,15 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
 
 // The preparation both operators share: list of the rows of at least min_len
 // entries, their window pointers, and (zero_rows) zeros in their rows of C.
-hipError_t launch_panel_preparation(const SpmmArgs& a, int32_t min_len, int64_t window_bytes, bool zero_rows,
-                                    int compute_units, hipStream_t s, PanelScratch** scratch, int* windows)
+// tile_cols = columns of B one item reads per row (a window holds window_bytes of such pieces).
+hipError_t launch_panel_preparation(const SpmmArgs& a, int64_t tile_cols, int32_t min_len, int64_t window_bytes,
+                                    bool zero_rows, int compute_units, hipStream_t s, PanelScratch** scratch,
+                                    int* windows)
 {
     PanelScratch* scr = panel_scratch();
     if (!scr) return hipErrorInvalidValue;
     int32_t window_rows = 1;
-    plan_panels(a.K, a.N, window_bytes, windows, &window_rows);
+    plan_panels(a.K, tile_cols, window_bytes, windows, &window_rows);
     hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
     hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
                        min_len);
@@ -308,13 +320,18 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
                                    int64_t window_bytes, hipStream_t s)
 {
     if (vec != 4 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
+    // one wavefront per item: chunk lanes for the columns of a tile (at most kPanelTileLanes * 4), the rest
+    // of the 64 lanes split the entries
+    int wave_lc = 1;
+    while (wave_lc < kPanelTileLanes && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
+    const int64_t window_cols = (int64_t)wave_lc * 4 < a.N ? (int64_t)wave_lc * 4 : a.N;
+    if ((a.N + window_cols - 1) / window_cols * kPanelMaxWindows * kPanelMaxRows > 0xffffffffLL)
+        return hipErrorInvalidValue;
     PanelScratch* scr = nullptr;
     int windows = 1;
-    hipError_t err = launch_panel_preparation(a, min_len, window_bytes, true, compute_units, s, &scr, &windows);
+    hipError_t err =
+        launch_panel_preparation(a, window_cols, min_len, window_bytes, true, compute_units, s, &scr, &windows);
     if (err != hipSuccess) return err;
-    // one wavefront per item: chunk lanes for the columns of one pass, the rest of the 64 lanes split the entries
-    int wave_lc = 1;
-    while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
     switch (wave_lc) {
         case 1: launch_long_rows<64, 1, 4>(a, scr, windows, xcds, compute_units, s); break;
         case 2: launch_long_rows<32, 2, 4>(a, scr, windows, xcds, compute_units, s); break;
@@ -489,7 +506,7 @@ hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, i
     if (a.N % 4 != 0 || a.N < 32 || a.N > 256 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
     PanelScratch* scr = nullptr;
     int windows = 1;
-    hipError_t err = launch_panel_preparation(a, min_len, window_bytes, false, compute_units, s, &scr, &windows);
+    hipError_t err = launch_panel_preparation(a, a.N, min_len, window_bytes, false, compute_units, s, &scr, &windows);
     if (err != hipSuccess) return err;
     int wave_lc = 8;
     while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
