@@ -38,7 +38,7 @@ MEASURED_TRAFFIC_BYTES: dict = {
     ("skewed", 64, "serial", "nnz_balanced"): 59_904_989_739,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
     ("powerlaw", 16, "serial", "nnz_balanced"): 242_820_253,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
     # --long-row-min 1024: all five kernels of the call, profiles/panel_long_rows_kernel_skewed.md
-    ("skewed", 4, "serial", "row_split", 1024): 7_657_730_804,
+    ("skewed", 4, "serial", "row_split", 1024): 7_695_174_915,
 }
 
 
@@ -46,6 +46,8 @@ MEASURED_TRAFFIC_BYTES: dict = {
 MEASURED_SDDMM_TRAFFIC_BYTES: dict = {
     ("stencil27", 8, "parallel"): 4_622_814_612,   # profiles/sddmm_rowcache_kernel_stencil27.md
     ("rmat", 8, "parallel"): 4_640_438_673,        # profiles/sddmm_rowcache_kernel_rmat.md
+    # --long-row-min 1024: all five kernels of the call, profiles/panel_sddmm_kernel_skewed.md
+    ("skewed", 16, "parallel", 1024): 8_349_418_150,
 }
 
 
