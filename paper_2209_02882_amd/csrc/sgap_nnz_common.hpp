@@ -220,16 +220,27 @@ __device__ __forceinline__ void merge_write_out(const SpmmArgs& a, const MergeBu
     for (int s = threadIdx.x / LC; s < mb.nslots; s += SLOT_LANES) {
         const int32_t row = mb.slot_row[s];
         if (row < 0) continue;
-        float* src = mb.accum + s * mb.width + chunk * VEC;
-        Vec<VEC> x;
+        if (mb.slot_atomic[s]) {
+            // atomic adds over consecutive words: an instruction whose lanes are 16 bytes apart
+            // costs four times as much, and out of LDS any lane can take any column
+            float* src = mb.accum + s * mb.width;
+            const int64_t k0 = k - (int64_t)chunk * VEC;  // first column of this pass
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            x.v[i] = src[i];
-            src[i] = 0.0f;
-        }
-        if (k_ok) {
-            float* __restrict__ dst = a.C + (int64_t)row * a.N + k;
-            if (mb.slot_atomic[s]) atomic_add_vec<VEC>(dst, x); else store_vec_stream<VEC>(dst, x);
+            for (int q = 0; q < VEC; ++q) {
+                const int col = q * LC + chunk;
+                const float x = src[col];
+                src[col] = 0.0f;
+                if (k0 + col < a.N) unsafeAtomicAdd(a.C + (int64_t)row * a.N + k0 + col, x);
+            }
+        } else {
+            float* src = mb.accum + s * mb.width + chunk * VEC;
+            Vec<VEC> x;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                x.v[i] = src[i];
+                src[i] = 0.0f;
+            }
+            if (k_ok) store_vec_stream<VEC>(a.C + (int64_t)row * a.N + k, x);
         }
         if (chunk == 0) mb.slot_row[s] = -1;
     }

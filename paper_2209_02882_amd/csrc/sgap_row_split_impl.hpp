@@ -106,8 +106,28 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
                         for (int i = 0; i < VEC; ++i)
                             acc.v[i] = group_partial_sum<G, LC>(acc.v[i], reduce_members * LC);
                         // a sub-group whose first member has no entry of the row holds +0
-                        if ((member & (reduce_members - 1)) == 0 && k_ok && (uint32_t)member < p_end - p_begin)
-                            atomic_add_vec<VEC>(a.C + (row_first + row) * N + k, acc);
+                        const bool adds = (member & (reduce_members - 1)) == 0 && (uint32_t)member < p_end - p_begin;
+                        if constexpr (LC >= VEC) {
+                            // The LC chunk lanes of a member hold LC*VEC consecutive columns, VEC per
+                            // lane.  An atomic instruction whose lanes are 16 bytes apart costs four
+                            // times one over consecutive words (451 against 115 clocks of the memory
+                            // pipeline, measured), so the sums change hands first: in round q lane c
+                            // adds column q*LC + c, which lane (q*LC + c) / VEC of the member holds.
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q) {
+                                const int col = q * LC + chunk;
+                                float mine = 0.0f;
+#pragma unroll
+                                for (int v = 0; v < VEC; ++v) {
+                                    const float t = __shfl(acc.v[v], col / VEC, LC);
+                                    if (col % VEC == v) mine = t;
+                                }
+                                if (adds && k0 + col < k_tile_end)
+                                    unsafeAtomicAdd(a.C + (row_first + row) * N + k0 + col, mine);
+                            }
+                        } else {
+                            if (adds && k_ok) atomic_add_vec<VEC>(a.C + (row_first + row) * N + k, acc);
+                        }
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc.v[i] = group_tree_sum<G, LC>(acc.v[i]);
