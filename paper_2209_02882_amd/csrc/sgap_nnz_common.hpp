@@ -140,12 +140,41 @@ __device__ __forceinline__ void find_tile_rows(const SpmmArgs& a, const TileDeal
     __syncthreads();
 }
 
-template <int VEC>
+// One run's sum leaves the registers: a plain store when nobody else adds to the
+// row, else atomic adds.  The LC chunk lanes of an entry lane whose columns lie
+// inside N call this together.  They hold LC*VEC consecutive columns, VEC per
+// lane; an atomic instruction whose lanes are 16 bytes apart costs four times
+// one over consecutive words, so where the pass is complete (all LC lanes are
+// here) the sums change hands first: in round q lane c adds column q*LC + c,
+// which chunk lane (q*LC + c) / VEC holds.
+template <int LC, int VEC>
 __device__ __forceinline__ void write_out(const SpmmArgs& a, int32_t row, int64_t k, bool plain,
                                           const Vec<VEC>& x)
 {
     float* __restrict__ dst = a.C + (int64_t)row * a.N + k;
-    if (plain) store_vec<VEC>(dst, x); else atomic_add_vec<VEC>(dst, x);
+    if (plain) {
+        store_vec<VEC>(dst, x);
+        return;
+    }
+    if constexpr (LC >= VEC && VEC > 1) {
+        const int chunk = threadIdx.x % LC;
+        const int64_t k0 = k - (int64_t)chunk * VEC;  // first column of this pass
+        if (k0 + LC * VEC <= a.N) {                   // the same for all lanes of the pass
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+                const int col = q * LC + chunk;
+                float mine = 0.0f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float t = __shfl(x.v[v], col / VEC, LC);
+                    if (col % VEC == v) mine = t;
+                }
+                unsafeAtomicAdd(a.C + (int64_t)row * a.N + k0 + col, mine);
+            }
+            return;
+        }
+    }
+    atomic_add_vec<VEC>(dst, x);
 }
 
 // LDS accumulators of tile mode.  Slot s < nslots-1 belongs to the row whose

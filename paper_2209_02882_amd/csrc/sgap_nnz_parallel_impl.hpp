@@ -133,7 +133,7 @@ __device__ __forceinline__ void parallel_chunk(const SpmmArgs& a, const MergeBuf
                                            chunk == 0 && (meta & kMetaOwner), e[u].row, (meta & kMetaOutside) != 0);
                         }
                     } else {
-                        write_out<VEC>(a, e[u].row, k, (meta & kMetaPlain) != 0, x[u]);
+                        write_out<LC, VEC>(a, e[u].row, k, (meta & kMetaPlain) != 0, x[u]);
                     }
                 }
             }

@@ -110,7 +110,7 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                     } else {
                         // the whole row lies inside this aligned block: nobody else adds to it
                         const bool plain = row_begin >= blk && row_end <= blk + G;
-                        write_out<VEC>(a, row, k, plain, acc);
+                        write_out<LC, VEC>(a, row, k, plain, acc);
                     }
                     acc.zero();
                     if (p + 1 < blk_end) {
