@@ -72,9 +72,17 @@ __global__ void panel_reset_kernel(PanelScratch* scr)
 __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, PanelScratch* scr, int32_t min_len)
 {
     const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (row >= a.M) return;
-    if (a.rowptr[row + 1] - a.rowptr[row] >= min_len) {
-        const uint32_t i = atomicAdd(&scr->count, 1u);
+    const bool is_long = row < a.M && a.rowptr[row + 1] - a.rowptr[row] >= min_len;
+    // one counter update per wavefront: a returning atomic on one address takes about 0.1 us,
+    // and a matrix may have thousands of long rows
+    const unsigned long long mask = __ballot(is_long);
+    if (mask == 0) return;
+    const int lane = threadIdx.x % kWave;
+    uint32_t base = 0;
+    if (lane == __ffsll((long long)mask) - 1) base = atomicAdd(&scr->count, (uint32_t)__popcll(mask));
+    base = (uint32_t)__shfl((int)base, __ffsll((long long)mask) - 1, kWave);
+    if (is_long) {
+        const uint32_t i = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
         if (i < (uint32_t)kPanelMaxRows) scr->rows[i] = (int32_t)row;
     }
 }
