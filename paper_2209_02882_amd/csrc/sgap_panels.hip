@@ -144,72 +144,85 @@ constexpr int kPanelClaim = 16;  // items a workgroup takes from its die's count
 // the narrower gathers cost more than that saves (skewed: 3.46 ms at 64 lanes, 3.69 at 32, 4.11 at 16).
 constexpr int kPanelTileLanes = 64;
 
-// One item: the entries [p0, p1) of row `row` times the columns k0 .. k0 + LC*VEC
-// of B, multiplied out by one wavefront whose 64 lanes are G members x LC chunk
-// lanes: the members split the entries, the group tree-sums and member 0 adds
-// the partial row into C.  p0, p1, row and k0 are the same in all lanes.
+// acc += the entries [p0, p1) times the columns k0 .. k0 + LC*VEC of B, for this
+// lane's member (the members split the entries) and chunk of columns.
 template <int G, int LC, int VEC, bool OFF32>
-__device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_t p1, int64_t row, int64_t k0, int lane)
+__device__ __forceinline__ void panel_accumulate(const SpmmArgs& a, Vec<VEC>& acc, int32_t p0, int32_t p1, int64_t k0,
+                                                 int lane)
 {
     constexpr int D = kPanelDepth;
     const int member = lane / LC;
     const int chunk = lane % LC;
-    {
-        const int64_t k = k0 + (int64_t)chunk * VEC;
-        const bool k_ok = k < a.N;
-        const BRow<OFF32> brow(a.B, a.N, k_ok ? k : 0);
-        Vec<VEC> acc;
-        acc.zero();
-        for (int32_t base = p0; base < p1; base += kWave) {
-            // 64 entries with one coalesced load each for columns and values
-            int32_t my_col = 0, my_val = 0;
-            if (base + lane < p1) {
-                my_col = load_stream(a.colidx + base + lane);
-                my_val = __float_as_int(load_stream(a.vals + base + lane));
-            }
-            const int cnt = p1 - base < kWave ? p1 - base : kWave;
-            // member m takes entries m, m + G, ... of the 64
-            for (int j0 = 0; j0 < cnt; j0 += G * D) {
-                int32_t col[D];
-                float val[D];
-                Vec<VEC> b[D];
-#pragma unroll
-                for (int u = 0; u < D; ++u) {
-                    const int j = j0 + u * G + member;
-                    col[u] = from_lane<G == 1>(my_col, j & (kWave - 1));
-                    val[u] = __int_as_float(from_lane<G == 1>(my_val, j & (kWave - 1)));
-                    if (j >= cnt) val[u] = 0.0f;
-                }
-#pragma unroll
-                for (int u = 0; u < D; ++u) {
-                    b[u].zero();
-                    if (k_ok && j0 + u * G + member < cnt) b[u] = load_vec<VEC>(brow.at(col[u]));
-                }
-#pragma unroll
-                for (int u = 0; u < D; ++u) acc.fma(val[u], b[u]);
-            }
+    const int64_t k = k0 + (int64_t)chunk * VEC;
+    const bool k_ok = k < a.N;
+    const BRow<OFF32> brow(a.B, a.N, k_ok ? k : 0);
+    for (int32_t base = p0; base < p1; base += kWave) {
+        // 64 entries with one coalesced load each for columns and values
+        int32_t my_col = 0, my_val = 0;
+        if (base + lane < p1) {
+            my_col = load_stream(a.colidx + base + lane);
+            my_val = __float_as_int(load_stream(a.vals + base + lane));
         }
+        const int cnt = p1 - base < kWave ? p1 - base : kWave;
+        // member m takes entries m, m + G, ... of the 64
+        for (int j0 = 0; j0 < cnt; j0 += G * D) {
+            int32_t col[D];
+            float val[D];
+            Vec<VEC> b[D];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc.v[v] = group_tree_sum<G, LC>(acc.v[v]);
-        // Member 0's LC lanes hold the LC*VEC consecutive columns of this pass, VEC per
-        // lane.  An atomic instruction whose lanes are 16 bytes apart keeps the memory
-        // pipeline busy 2.5 times longer than one over consecutive words (290 against
-        // 115 clocks, measured), so the sums change hands first, which also makes the
-        // instructions as few as they can be: in round q lane l adds column q*64 + l,
-        // which lane (q*64 + l) / VEC holds (lanes 0 .. LC-1 are member 0).
-        constexpr int PASS = LC * VEC;
-#pragma unroll
-        for (int q = 0; q < (PASS + kWave - 1) / kWave; ++q) {
-            const int col = q * kWave + lane;  // column of this pass, counted from k0
-            float mine = 0.0f;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                const float t = __shfl(acc.v[v], (col / VEC) & (kWave - 1), kWave);
-                if (col % VEC == v) mine = t;
+            for (int u = 0; u < D; ++u) {
+                const int j = j0 + u * G + member;
+                col[u] = from_lane<G == 1>(my_col, j & (kWave - 1));
+                val[u] = __int_as_float(from_lane<G == 1>(my_val, j & (kWave - 1)));
+                if (j >= cnt) val[u] = 0.0f;
             }
-            if (col < PASS && k0 + col < a.N) unsafeAtomicAdd(a.C + row * a.N + k0 + col, mine);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                b[u].zero();
+                if (k_ok && j0 + u * G + member < cnt) b[u] = load_vec<VEC>(brow.at(col[u]));
+            }
+#pragma unroll
+            for (int u = 0; u < D; ++u) acc.fma(val[u], b[u]);
         }
     }
+}
+
+// The members' partial sums of one row piece, tree-summed and added into C.
+// Member 0's LC lanes hold the LC*VEC consecutive columns of the tile, VEC per
+// lane.  An atomic instruction whose lanes are 16 bytes apart keeps the memory
+// pipeline busy four times longer than one over consecutive words (451 against
+// 115 clocks, measured), so the sums change hands first, which also makes the
+// instructions as few as they can be: in round q lane l adds column q*64 + l,
+// which lane (q*64 + l) / VEC holds (lanes 0 .. LC-1 are member 0).
+template <int G, int LC, int VEC>
+__device__ __forceinline__ void panel_flush(const SpmmArgs& a, Vec<VEC> acc, int64_t row, int64_t k0, int lane)
+{
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc.v[v] = group_tree_sum<G, LC>(acc.v[v]);
+    constexpr int PASS = LC * VEC;
+#pragma unroll
+    for (int q = 0; q < (PASS + kWave - 1) / kWave; ++q) {
+        const int col = q * kWave + lane;  // column of the tile, counted from k0
+        float mine = 0.0f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const float t = __shfl(acc.v[v], (col / VEC) & (kWave - 1), kWave);
+            if (col % VEC == v) mine = t;
+        }
+        if (col < PASS && k0 + col < a.N) unsafeAtomicAdd(a.C + row * a.N + k0 + col, mine);
+    }
+}
+
+// One item: the entries [p0, p1) of row `row` times the columns k0 .. k0 + LC*VEC
+// of B, multiplied out by one wavefront whose 64 lanes are G members x LC chunk
+// lanes.  p0, p1, row and k0 are the same in all lanes.
+template <int G, int LC, int VEC, bool OFF32>
+__device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_t p1, int64_t row, int64_t k0, int lane)
+{
+    Vec<VEC> acc;
+    acc.zero();
+    panel_accumulate<G, LC, VEC, OFF32>(a, acc, p0, p1, k0, lane);
+    panel_flush<G, LC, VEC>(a, acc, row, k0, lane);
 }
 
 // B is cut into blocks of one window of rows by one tile of LC*VEC columns
