@@ -264,6 +264,9 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J,
  *          schedule (row-split first), strategy (parallel first), group size
  *          ascending.
  *   best   host, not NULL: the fastest point.
+ * The tuning knobs in force (sgap_set_tuning) apply to the timed launches, so
+ * a tuner run with SGAP_TUNE_LONG_ROW_MIN set rates the row-split points with
+ * their long rows taken by column windows.
  * The call blocks until the measurements are done (it synchronises `stream`),
  * allocates no device memory and leaves in C the result of the fastest point,
  * computed last.  M == 0 or N == 0: nothing to time, SGAP_ERR_INVALID_ARG.
