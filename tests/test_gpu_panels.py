@@ -249,3 +249,16 @@ def test_sddmm_full_size_skewed_every_entry(panels):
         assert not torch.isnan(out).any(), f"g={g} {st}: entry never written"
         bad = (out.double() - ref_t).abs() > TOL * bnd_t
         assert not bool(bad.any()), f"g={g} {st}: {int(bad.sum())} entries out of tolerance"
+
+
+def test_ttm_takes_the_window_path_through_the_spmm_kernels(panels):
+    # TTM along the last index is SpMM over the stored fibers: long fibers go window by window too
+    from paper_2209_02882_amd.device import DeviceTensor3
+    from test_gpu_tensor import tensor_from
+
+    p = tensor_from(40, 300, 6000, 64, [5] * 40, [3, 900, 7, 2500, 1], 33, integer=True)
+    ref, bnd = oracle.ttm_csf(p.I, p.K, p.L, p.J, p.fptr, p.fidx, p.eptr, p.eidx, p.vals, p.X2, nthreads=8)
+    dt = DeviceTensor3(p)
+    panels(500, 64)
+    for point in [(1, "serial", "row_split"), (8, "parallel", "row_split"), (16, "serial", "nnz_balanced")]:
+        assert_close(dt.run_ttm(*point), ref, bnd, exact=True, what=f"ttm with windows {point}")
