@@ -221,3 +221,31 @@ def test_serial_plan_keeps_partial_sums_on_chip_and_fills_the_chip():
     assert plan(16, 8, 2, 10_240)[0] == 1024
     assert plan(16, 8, 4, 10_240, forced=2048)[0] == 2048
     assert lib.sgap_debug_plan_nnz_serial(3, 8, 4, 0, 256, 0, None, None) == binding.SGAP_ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 without warnings,
+    # and a C program must link against the built library (it is not run: no GPU here)
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_sgap.c"
+    src.write_text(
+        '#include "sgap.h"\n'
+        "int main(void)\n{\n"
+        "    float c[4];\n"
+        "    int rc = sgap_spmm_csr(0, 0, 0, 0, 0, 0, 0, c, 8, SGAP_REDUCE_PARALLEL, 0);\n"
+        "    return rc == SGAP_OK && sgap_version() >= 100 ? 0 : 1;\n"
+        "}\n")
+    inc = os.path.join(root, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-fsyntax-only", str(src)],
+                   check=True)
+    binding.load()  # raises if the library has not been built
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    exe = tmp_path / "use_sgap"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", lib_dir, "-lsgap",
+                    "-Wl,--unresolved-symbols=ignore-in-shared-libs"], check=True)
+    assert exe.exists()
