@@ -111,8 +111,10 @@ def test_other_schedules_and_unaligned_operands_ignore_the_knob(panels):
         binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, -1)
 
 
-def test_full_size_skewed_sampled_rows(panels):
-    p = wl.make_problem("skewed")
+@pytest.mark.parametrize("name", ["skewed", "rmat"])
+def test_full_size_sampled_rows(panels, name):
+    # skewed: 1 KB rows of B, one member per wavefront; rmat: 128-byte rows, eight members, hub rows of 86,000 entries
+    p = wl.make_problem(name)
     dp = DeviceProblem(p)
     rows = sample_rows(p)
     C_ref, BND = oracle.spmm_csr_rows(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, rows)
