@@ -69,3 +69,30 @@ def test_full_size_sddmm_every_entry(name):
             assert not torch.isnan(out).any(), f"{name} sddmm g={g} {st}: entry never written"
             bad = (out.double() - ref_t).abs() > TOL * bnd_t
             assert not bool(bad.any()), f"{name} sddmm g={g} {st}: {int(bad.sum())} entries out of tolerance"
+
+
+def test_twenty_million_short_rows():
+    # many rows, few entries each, four dense columns: grids of more than a million workgroups,
+    # row and entry counts far beyond 16 bits, C of 320 MB written four bytes per lane
+    M, K, N = 20_000_000, 1000, 4
+    rng = np.random.default_rng(77)
+    lengths = rng.integers(0, 4, size=M)
+    lengths[rng.integers(0, M, size=50)] = 900  # a few rows that span many tiles
+    rowptr, colidx = wl.csr_from_lengths(rng, lengths.astype(np.int64), K)
+    vals = wl.fill_values(rng, colidx.size, True)
+    B = wl.fill_values(rng, K * N, True).reshape(K, N)
+    p = wl.SpmmProblem("many_rows", M, K, N, rowptr, colidx, vals, B)
+    print(p.row_stats(), flush=True)
+    rows = sample_rows(p, n_random=5000)
+    C_ref, _ = oracle.spmm_csr_rows(M, K, N, rowptr, colidx, vals, B, rows)
+    dp = DeviceProblem(p)
+    rows_t = torch.from_numpy(rows).cuda()
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    for point in [(1, "serial", "row_split"), (4, "parallel", "row_split"), (64, "parallel", "row_split"),
+                  (8, "serial", "nnz_balanced"), (64, "serial", "nnz_balanced"), (16, "parallel", "nnz_balanced"),
+                  (1, "parallel", "nnz_balanced")]:
+        print("  point", point, flush=True)
+        dp.run(*point, C=C)
+        assert not torch.isnan(C).any(), f"{point}: element never written"
+        got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, C_ref), f"{point}: {int((got != C_ref).sum())} sampled elements differ"
