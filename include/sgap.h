@@ -33,6 +33,9 @@
  *     0 <= colidx[p] < K.  Column indices inside a row need not be sorted
  *     or distinct (duplicates add).  Explicit zeros are ordinary entries.
  *   - Indices are 0-based int32; element offsets are formed in 64 bits.
+ *     Positions of stored entries are 32-bit: rowptr[M] may be at most
+ *     2^31 - 65,536 (2,147,418,112; a hint beyond that is refused), which
+ *     leaves room for the kernels to step past the end by a tile.
  *   - Semantics are OVERWRITE (C = A*B): rows without stored entries become
  *     +0, whatever C held before.  A row's result may be -0 or +0 where the
  *     exact sum is zero.

@@ -179,6 +179,7 @@ int pow2_ceil_capped(int64_t v, int cap)
 }
 
 constexpr int kXcds = 8;            // accelerator dies, each with its own L2
+constexpr int64_t kMaxEntries = 2147483647LL - 65535;  // 32-bit positions with room for a tile past the end
 constexpr int kAutoTileCols = 128;  // 512 bytes of a B row per work item
 
 int compute_units()
@@ -210,6 +211,7 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
         return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
     if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
+    if (nnz_hint > kMaxEntries) return fail(SGAP_ERR_INVALID_ARG, "more stored entries than 2^31 - 65536");
     if (reduce_size != 0 && (!is_pow2_group(reduce_size) || reduce_size > group_size))
         return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
     if (reduce_size == group_size) reduce_size = 0;
@@ -347,6 +349,7 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     if (strategy != SGAP_REDUCE_PARALLEL && strategy != SGAP_REDUCE_SERIAL)
         return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
     if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
+    if (nnz_hint > kMaxEntries) return fail(SGAP_ERR_INVALID_ARG, "more stored entries than 2^31 - 65536");
     if (M == 0 || nnz_hint == 0) return SGAP_OK;
     if (!rowptr) return fail(SGAP_ERR_INVALID_ARG, "rowptr must not be null");
     if (!colidx || !vals || !out_vals) {

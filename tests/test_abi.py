@@ -141,6 +141,15 @@ def test_validate_arguments_are_checked_without_launch():
     assert b"null" in lib.sgap_last_error()
 
 
+def test_entry_counts_beyond_the_position_range_are_refused():
+    lib = binding.load()
+    ptrs = [0x1000 * i for i in range(1, 6)]
+    assert lib.sgap_spmm_csr_ex(4, 4, 4, *ptrs, 8, 0, 0, 2**31 - 65535, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"2^31" in lib.sgap_last_error()
+    assert lib.sgap_sddmm_csr(4, 4, 4, 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 8, 0, 2**31 - 1, None) \
+        == binding.SGAP_ERR_INVALID_ARG
+
+
 def test_empty_shapes_are_ok_without_launch():
     lib = binding.load()
     assert lib.sgap_spmm_csr_ex(0, 5, 8, None, None, None, None, None, 8, 0, 0, -1, None) == 0

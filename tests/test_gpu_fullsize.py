@@ -96,3 +96,54 @@ def test_twenty_million_short_rows():
         assert not torch.isnan(C).any(), f"{point}: element never written"
         got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
         assert np.array_equal(got, C_ref), f"{point}: {int((got != C_ref).sum())} sampled elements differ"
+
+
+def test_two_billion_stored_entries():
+    # positions close to the end of the int32 range: 2,000,000 rows of 1,024 entries = 2,048,000,000 entries
+    # (16 GB of columns and values, made on the device from a formula the host can repeat for sampled rows)
+    M, per_row, K, N = 2_000_000, 1024, 4096, 32
+    nnz = M * per_row
+    assert nnz < 2**31 - 65536
+    dev = torch.device("cuda:0")
+    if torch.cuda.get_device_properties(dev).total_memory < 40 * 2**30:
+        pytest.skip("needs 40 GB of device memory")
+    rowptr = (torch.arange(M + 1, dtype=torch.int64, device=dev) * per_row).to(torch.int32)
+    pos = torch.arange(nnz, dtype=torch.int64, device=dev)
+    colidx = ((pos // per_row) * 7 + (pos % per_row) * 13).remainder_(K).to(torch.int32)
+    vals = ((pos // per_row + pos % per_row).remainder_(5) - 2).to(torch.float32)
+    del pos
+    rng = np.random.default_rng(5)
+    B = wl.fill_values(rng, K * N, True).reshape(K, N)
+    Bd = torch.from_numpy(B).to(dev)
+    rows = np.unique(np.concatenate([rng.integers(0, M, size=300), [0, 1, M - 2, M - 1]]))
+    j = np.arange(per_row)
+    C_ref = np.zeros((rows.size, N))
+    for n, r in enumerate(rows):
+        cols = (r * 7 + j * 13) % K
+        v = ((r + j) % 5 - 2).astype(np.float64)
+        C_ref[n] = v @ B[cols].astype(np.float64)
+    rows_t = torch.from_numpy(rows).to(dev)
+    C = torch.empty((M, N), dtype=torch.float32, device=dev)
+    for point in [(1, "serial", "row_split"), (16, "parallel", "row_split"), (16, "serial", "nnz_balanced"),
+                  (64, "serial", "nnz_balanced"), (8, "parallel", "nnz_balanced")]:
+        print("  point", point, flush=True)
+        C.fill_(float("nan"))
+        binding.sgap_spmm_csr_ex(M, K, N, rowptr, colidx, vals, Bd, C, point[0], binding.STRATEGIES[point[1]],
+                                 binding.SCHEDULES[point[2]])
+        torch.cuda.synchronize()
+        assert not torch.isnan(C).any(), f"{point}: element never written"
+        got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, C_ref), f"{point}: {int((got != C_ref).sum())} sampled elements differ"
+    # the SDDMM on the same pattern, one point
+    X1 = torch.from_numpy(wl.fill_values(rng, 64 * N, True).reshape(64, N)).to(dev).repeat(M // 64, 1).contiguous()
+    out = torch.full((nnz,), float("nan"), dtype=torch.float32, device=dev)
+    binding.sgap_sddmm_csr(M, K, N, rowptr, colidx, vals, X1, Bd, out, 8, binding.STRATEGIES["parallel"])
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any()
+    X1h = X1[:64].cpu().numpy().astype(np.float64)
+    outh = out.view(M, per_row).index_select(0, rows_t).cpu().numpy().astype(np.float64)
+    for n, r in enumerate(rows):
+        cols = (r * 7 + j * 13) % K
+        v = ((r + j) % 5 - 2).astype(np.float64)
+        ref = v * (B[cols].astype(np.float64) @ X1h[r % 64])
+        assert np.array_equal(outh[n], ref), f"sddmm row {r}"
