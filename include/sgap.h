@@ -15,19 +15,28 @@
  * Conventions for every entry point
  *   - All array arguments are DEVICE pointers owned by the caller.  The
  *     library reads rowptr/colidx/vals/B, overwrites C, keeps no pointer
- *     after the call returns and allocates no device memory.  (Two paths
- *     keep working data in file-scope device arrays of the library, one copy
- *     per GPU: the long-rows-by-windows path, see SGAP_TUNE_LONG_ROW_MIN, and
- *     sgap_validate_csr.  Calls that use one of them must not overlap on one
- *     GPU; all other calls may run concurrently on different streams.)
+ *     after the call returns and allocates no device memory.  The one path
+ *     that needs working memory (long rows by column windows, see
+ *     sgap_spmm_csr_cfg) takes it from the caller, who may use it for
+ *     something else once the work enqueued by the call has finished; calls
+ *     that are given different workspaces may run concurrently on different
+ *     streams.  (sgap_validate_csr keeps four counters in a file-scope device
+ *     array of the library, one copy per GPU: calls to it must not overlap on
+ *     one GPU.)
+ *   - The library keeps a little host-side state without locks (the schedule
+ *     and tuning defaults, cached device properties, the profiling event
+ *     list): call it from one host thread at a time; any number of streams.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and the call returns without waiting.
  *   - A call only enqueues kernels (no allocation, no host synchronisation, no
  *     memset nodes), so it may be recorded into a HIP graph; the first call
  *     that uses a kernel instance asks the runtime for its occupancy and
  *     should be made once outside a capture.
- *   - Return value: an sgap_status.  On anything but SGAP_OK nothing was
- *     launched and C is untouched; sgap_last_error() gives detail.
+ *   - Return value: an sgap_status.  SGAP_ERR_INVALID_ARG and
+ *     SGAP_ERR_UNSUPPORTED are found before anything is launched and leave C
+ *     untouched; after SGAP_ERR_HIP (the runtime refused a launch) some of the
+ *     call's kernels may already be enqueued and the contents of C are
+ *     undefined.  sgap_last_error() gives detail.
  *   - Preconditions that are NOT checked on the device: rowptr[0] == 0,
  *     rowptr non-decreasing, rowptr[M] == number of stored entries,
  *     0 <= colidx[p] < K.  Column indices inside a row need not be sorted
@@ -159,6 +168,104 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N,
                      int group_size, int reduce_size, int64_t nnz_hint, void* stream);
 
 /*
+ * Per-call configuration: the point of the design space (schedule, strategy,
+ * group_size, reduce_size as for the calls above) together with the tiling
+ * parameters that the paper tunes apart from the synchronisation granularity
+ * (Section 7.2: the space <groupSz, blockSz, tileSz, workerDimR> of Tables 4
+ * and 5; here group_size, block_size, tile_cols and rows_per_group).  Zero
+ * (-1 for xcd_remap) leaves a choice to the library.  None of them changes the
+ * result beyond the order of fp32 additions.
+ *   reduce_size     0 or group_size: the whole group reduces; a smaller power
+ *                   of two: sub-groups merged with atomics (row-split schedule,
+ *                   parallel strategy only; see sgap_spmm_csr_gr).
+ *   block_size      threads per workgroup of the row-split schedule: 128, 256
+ *                   or 512 (automatic: 256).  block_size / (lanes per row x
+ *                   lanes per column tile) groups work side by side on
+ *                   neighbouring rows.
+ *   tile_cols       columns of B/C per work item of the row-split schedule
+ *                   (rounded up to the vector width, capped at N; automatic:
+ *                   128); with the vector width it fixes the lanes that share
+ *                   a row of B, hence how many rows a workgroup works on at once.
+ *   rows_per_group  rows one group works through per work item in the row-split
+ *                   parallel strategy (the serial strategy takes group_size rows
+ *                   by definition); automatic: from the mean row length.
+ *   xcd_remap       1/-1: hand each of the 8 dies a contiguous run of work items
+ *                   so that its L2 keeps the rows of B it gathers; 0: plain
+ *                   round-robin order.
+ *   persistent      1: the row-split schedule launches only as many workgroups
+ *                   as the chip holds at once and each loops over work items.
+ *   nnz_tile        stored entries per tile of the nnz-balanced serial strategy:
+ *                   256, 512, 1024 or 2048 (the two small ones need N % 4 == 0
+ *                   and 16-byte aligned B and C, else the automatic choice is kept).
+ *   wave_rows       reserved, must be 0.
+ *   long_row_min    row-split schedule, reduce_size = group_size, N % 4 == 0 and
+ *                   16-byte aligned B and C only (ignored otherwise): rows of at
+ *                   least this many stored entries (say 1024) are taken out of the
+ *                   row-split kernel and produced by column windows: the columns
+ *                   are cut into windows of window_kb KiB of B, a die works on one
+ *                   window at a time so that its L2 serves the gathers, and the
+ *                   pieces of a long row are added into C with atomic adds (the
+ *                   "Atomics" output strategy of Section 6.2; fp32 rounding then
+ *                   varies between runs, as on the nnz-balanced schedule).  Worth
+ *                   it when long rows hold most entries and B is far larger than
+ *                   the L2s.  Needs a workspace (below).  0 = off.
+ *   window_kb       KiB of B per column window (at most 511 windows are made);
+ *                   automatic: 3072.
+ *   max_long_rows   capacity of the list of long rows, at most 1,048,576;
+ *                   automatic: 8192.  The rows are found on the device; when a
+ *                   matrix has more long rows than this, the call produces every
+ *                   row with the row-split kernel instead (correct, slower).
+ */
+typedef struct {
+    int schedule;
+    int strategy;
+    int group_size;
+    int reduce_size;
+    int block_size;
+    int tile_cols;
+    int rows_per_group;
+    int xcd_remap;
+    int persistent;
+    int nnz_tile;
+    int wave_rows;
+    int long_row_min;
+    int window_kb;
+    int max_long_rows;
+} sgap_config;
+
+/* Fill *config with the defaults: row-split schedule, parallel strategy, group
+ * size 8, every tiling choice left to the library, long rows not set apart. */
+int sgap_config_init(sgap_config* config);
+
+/*
+ * Bytes of device workspace that sgap_spmm_csr_cfg needs for this shape and
+ * configuration: 0 when long_row_min is 0 (or the window path cannot apply:
+ * another schedule, reduce_size < group_size, N % 4 != 0), else a 256-byte
+ * header plus 4 * max_long_rows * (windows + 3) bytes, where windows =
+ * ceil(K / rows of B per window).  Returns -1 for invalid arguments.
+ */
+int64_t sgap_spmm_csr_workspace_size(int64_t M, int64_t K, int64_t N, const sgap_config* config);
+
+/*
+ * C = A*B at the point and with the tiling that *config names (host pointer,
+ * read during the call only).  Arguments, ownership and errors as for
+ * sgap_spmm_csr_ex, and:
+ *   workspace        device memory, 256-byte aligned, at least
+ *                    sgap_spmm_csr_workspace_size(M, K, N, config) bytes; may be
+ *                    NULL when that is 0.  The call's kernels write and read it;
+ *                    its contents afterwards mean nothing to the caller.  Two
+ *                    calls that may run at the same time need two workspaces.
+ *   workspace_bytes  its size; a size below the need is SGAP_ERR_INVALID_ARG.
+ * The call only enqueues kernels on `stream`: no allocation, no host
+ * synchronisation, no memset node.
+ */
+int sgap_spmm_csr_cfg(int64_t M, int64_t K, int64_t N,
+                      const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                      const float* B, float* C,
+                      const sgap_config* config, int64_t nnz_hint,
+                      void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Sampled dense-dense matrix product on the pattern of a CSR matrix, the
  * SDDMM form of the paper's Section 2.1 (third form under Eq. 1):
  *   out_vals[p] = vals[p] * sum_{j<J} X1[row(p), j] * X2T[colidx[p], j]
@@ -187,6 +294,29 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J,
                    const int32_t* rowptr, const int32_t* colidx, const float* vals,
                    const float* X1, const float* X2T, float* out_vals,
                    int group_size, int strategy, int64_t nnz_hint, void* stream);
+
+/*
+ * The same product with the stored entries of long rows taken by column
+ * windows of X2T, as sgap_spmm_csr_cfg does for SpMM (same reasoning: a die
+ * works on one window at a time so that its L2 serves the gathered rows of
+ * X2T).  Applies when J % 4 == 0, 32 <= J <= 256 and X1, X2T are 16-byte
+ * aligned; otherwise the call is sgap_sddmm_csr.  Every entry still has one
+ * writer: no atomics, results reproducible.
+ *   long_row_min, window_kb (automatic: 2048), max_long_rows
+ *                    as in sgap_config
+ *   workspace, workspace_bytes
+ *                    device memory, 256-byte aligned, of at least
+ *                    sgap_sddmm_csr_workspace_size(K, J, window_kb,
+ *                    max_long_rows) bytes (0: the path does not apply; -1:
+ *                    invalid arguments)
+ */
+int sgap_sddmm_csr_windows(int64_t M, int64_t K, int64_t J,
+                           const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                           const float* X1, const float* X2T, float* out_vals,
+                           int group_size, int strategy, int64_t nnz_hint,
+                           int long_row_min, int window_kb, int max_long_rows,
+                           void* workspace, int64_t workspace_bytes, void* stream);
+int64_t sgap_sddmm_csr_workspace_size(int64_t K, int64_t J, int window_kb, int max_long_rows);
 
 /*
  * Tensor-times-matrix product along the last index of a third-order sparse
@@ -267,9 +397,7 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J,
  *          schedule (row-split first), strategy (parallel first), group size
  *          ascending.
  *   best   host, not NULL: the fastest point.
- * The tuning knobs in force (sgap_set_tuning) apply to the timed launches, so
- * a tuner run with SGAP_TUNE_LONG_ROW_MIN set rates the row-split points with
- * their long rows taken by column windows.
+ * The tuning defaults in force (sgap_set_tuning) apply to the timed launches.
  * The call blocks until the measurements are done (it synchronises `stream`),
  * allocates no device memory and leaves in C the result of the fastest point,
  * computed last.  M == 0 or N == 0: nothing to time, SGAP_ERR_INVALID_ARG.
@@ -287,6 +415,42 @@ int sgap_autotune_csr(int64_t M, int64_t K, int64_t N,
                       const float* B, float* C, int64_t nnz_hint, int reps,
                       sgap_point_time* table, sgap_point_time* best, void* stream);
 
+/*
+ * The tuner over the whole space the library has (Section 7.2 tunes
+ * <groupSz, blockSz, tileSz, workerDimR> per matrix, Tables 4 and 5).  Rates,
+ * in this order: the SGAP_NUM_POINTS points above; the 21 row-split points
+ * with the reduction narrower than the tiling (group_size 2..64, reduce_size
+ * below it: Table 1); if `workspace` covers the default window and list
+ * (sgap_spmm_csr_workspace_size with long_row_min > 0, window_kb = 0,
+ * max_long_rows = 0), the row-split points with group sizes 1 to 8 of both
+ * strategies with the long rows by column windows (long_row_min 512 and
+ * 2048); then, around the fastest configuration so far, one knob at a time:
+ * block_size 128 and 512, tile_cols 32, 64, 256, rows_per_group 1 to 16
+ * (row-split parallel), window_kb 2048 and 4096 (window path, where the
+ * workspace covers it), or nnz_tile 512, 1024, 2048 (nnz-balanced serial).
+ * Timing of one configuration as in sgap_autotune_csr.
+ *   workspace, workspace_bytes  as for sgap_spmm_csr_cfg; NULL/0: the window
+ *          path is not rated
+ *   table  host, NULL or room for `capacity` entries; the first `capacity`
+ *          rated configurations in the order above
+ *   count  host or NULL: how many configurations were rated (may exceed
+ *          capacity; at most SGAP_MAX_TUNED_POINTS)
+ *   best   host, not NULL: the fastest configuration and its time; it can be
+ *          handed to sgap_spmm_csr_cfg as it is
+ * Blocks, allocates nothing and leaves the fastest configuration's result in C.
+ */
+#define SGAP_MAX_TUNED_POINTS 96
+typedef struct {
+    sgap_config config;
+    float ms;
+} sgap_tuned_point;
+int sgap_autotune_csr_cfg(int64_t M, int64_t K, int64_t N,
+                          const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                          const float* B, float* C, int64_t nnz_hint, int reps,
+                          void* workspace, int64_t workspace_bytes,
+                          sgap_tuned_point* table, int capacity, int* count,
+                          sgap_tuned_point* best, void* stream);
+
 /* Text for a status code / detail of this thread's last failure (static or
  * thread-local storage; never free). */
 const char* sgap_status_string(int status);
@@ -296,10 +460,12 @@ const char* sgap_last_error(void);
 int sgap_version(void);
 
 /*
- * Tuning overrides in the spirit of the paper's Section 7.2 (tiling
- * parameters are separate from the synchronisation granularity).  Process
- * wide, not thread-safe; value 0 (or -1 where stated) restores the automatic
- * choice.  They change speed only, never results beyond fp32 summation order.
+ * Process-wide defaults for the tiling choices of the entry points that take
+ * no sgap_config (sgap_spmm_csr, _ex, _gr, sgap_ttm_csf, sgap_autotune_csr),
+ * in the spirit of the paper's Section 7.2 (tiling parameters are separate
+ * from the synchronisation granularity).  Not thread-safe; value 0 (or -1
+ * where stated) restores the automatic choice.  They change speed only, never
+ * results beyond fp32 summation order.  sgap_spmm_csr_cfg ignores them.
  *   SGAP_TUNE_TILE_COLS  columns of B/C per work item of the row-split
  *                        schedule (rounded up to the vector width, capped at
  *                        N); 0 = automatic.
@@ -325,29 +491,9 @@ int sgap_version(void);
  *                        the current row of X1 in registers when
  *                        J <= 16 * group_size and the operands are 16-byte
  *                        aligned; 0: every entry loads both of its rows.
- *   SGAP_TUNE_LONG_ROW_MIN  row-split schedule, N % 4 == 0 and 16-byte aligned
- *                        B and C only: rows of at least this many stored
- *                        entries (say 1024) are taken out of the row-split
- *                        kernel and produced by column windows: the columns
- *                        are cut into windows of about 2 MiB of B, a die works
- *                        on one window at a time so that its L2 serves the
- *                        gathers, and every (window, long row) piece is added
- *                        into C with atomic adds (fp32 rounding then varies
- *                        between runs, as on the nnz-balanced schedule).
- *                        Worth it when long rows hold most entries and B is
- *                        far larger than the L2s.  This path keeps its list of
- *                        long rows (at most 8192; with more it switches itself
- *                        off for that call) and their window pointers in a
- *                        device array of the library, about 8.4 MB per GPU,
- *                        shared by all calls on that GPU: calls that use it
- *                        must not overlap on one GPU.  0 (default) = off.
- *                        sgap_sddmm_csr takes the same path for the stored
- *                        entries of such rows when J % 4 == 0, 32 <= J <= 256
- *                        and X1, X2T are 16-byte aligned (no atomics there:
- *                        every entry still has one writer); all other entries
- *                        then go through the kernel without the row cache.
- *   SGAP_TUNE_PANEL_WINDOW_KB  KiB of B per column window of that path (at most
- *                        255 windows are made); 0 = automatic (2048).
+ * Knobs 6 and 7 (long rows by column windows) of earlier versions are gone:
+ * that path needs working memory and is chosen per call, see sgap_config;
+ * their numbers are refused with SGAP_ERR_INVALID_ARG.
  */
 typedef enum {
     SGAP_TUNE_TILE_COLS = 0,
@@ -355,61 +501,9 @@ typedef enum {
     SGAP_TUNE_ROWS_PER_GROUP = 2,
     SGAP_TUNE_PERSISTENT = 3,
     SGAP_TUNE_NNZ_TILE = 4,
-    SGAP_TUNE_SDDMM_ROW_CACHE = 5,
-    SGAP_TUNE_LONG_ROW_MIN = 6,
-    SGAP_TUNE_PANEL_WINDOW_KB = 7
+    SGAP_TUNE_SDDMM_ROW_CACHE = 5
 } sgap_tuning_knob;
 int sgap_set_tuning(int knob, int value);
-
-/*
- * Timing hooks for benchmarks.  While enabled, every sgap_spmm_csr* call
- * brackets its main SpMM kernel (not the row-zeroing pass) with a pair of HIP
- * events on the call's stream.  sgap_profile_collect waits for those events,
- * adds their elapsed times in milliseconds into *total_ms, their number into
- * *count, and forgets them.  Not thread-safe; host pointers.
- */
-int sgap_profile_enable(int on);
-int sgap_profile_collect(double* total_ms, int* count);
-
-/*
- * Device self-checks of the two cross-lane primitives behind the strategies
- * (the paper's macro instructions atomicAddGroup<T,G> and
- * segReduceGroup<T,G>, Section 5.3), one wavefront each.  `lanes_per_row`
- * (1..64/group_size, power of two) is the lane stride between neighbouring
- * members of a group.
- *   sgap_debug_group_reduce: in fp32[64] device -> out fp32[64] device; the
- *     first lane of every group receives the sum of its group's inputs, other
- *     lanes receive 0.
- *   sgap_debug_group_seg_reduce: in fp32[64], span int32[64] device (span[l] =
- *     how many following members of lane l's group continue lane l's run,
- *     0..group_size-1) -> out[l] = in[l] + the next span[l] members' inputs.
- *   sgap_debug_group_partial_reduce: the same for sub-groups of reduce_size
- *     members (power of two <= group_size): the first lane of every sub-group
- *     receives the sub-group's sum, other lanes 0.
- */
-int sgap_debug_group_reduce(const float* in, float* out, int group_size,
-                            int lanes_per_row, void* stream);
-int sgap_debug_group_partial_reduce(const float* in, float* out, int group_size,
-                                    int reduce_size, int lanes_per_row, void* stream);
-int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out,
-                                int group_size, int lanes_per_row, void* stream);
-
-/*
- * Host-side pieces of the nnz-balanced schedule, exported for tests; no GPU
- * is touched.
- *   sgap_debug_tile_deal: which tiles of stored entries workgroup `block` of a
- *     persistent grid of `grid` workgroups takes when the matrix has `tiles`
- *     tiles (chunks of neighbouring tiles per die).  Writes up to `capacity`
- *     tile numbers, ascending, into out_tiles (host) and returns how many
- *     tiles the workgroup takes, or -1 on bad arguments.
- *   sgap_debug_plan_nnz_serial: tile size (stored entries) and whether a
- *     tile's partial sums are merged on chip, for the serial strategy with
- *     lanes_per_row chunk lanes of cols_per_lane columns each on a chip of
- *     compute_units; forced_tile as SGAP_TUNE_NNZ_TILE.  Host pointers.
- */
-int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_tiles, int64_t capacity);
-int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
-                               int compute_units, int forced_tile, int* tile, int* merge_on_chip);
 
 /*
  * Check the preconditions that the compute calls rely on and cannot test
@@ -432,10 +526,6 @@ int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_l
  */
 int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, int64_t nnz,
                       int64_t* report, void* stream);
-
-/* Plain device-to-device fp32 copy kernel (n elements).  Used to calibrate
- * hardware traffic counters and to report a streaming-bandwidth reference. */
-int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream);
 
 #ifdef __cplusplus
 }

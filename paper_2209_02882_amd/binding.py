@@ -29,7 +29,7 @@ STRATEGY_NAMES = {v: k for k, v in STRATEGIES.items()}
 SCHEDULE_NAMES = {v: k for k, v in SCHEDULES.items()}
 GROUP_SIZES = (1, 2, 4, 8, 16, 32, 64)
 
-# every symbol include/sgap.h declares: name -> (restype, argtypes)
+# every symbol include/sgap.h and include/sgap_debug.h declare: name -> (restype, argtypes)
 _i64, _int, _p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
 EXPORTS = {
     "sgap_set_schedule": (_int, [_int]),
@@ -37,8 +37,15 @@ EXPORTS = {
     "sgap_spmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_spmm_csr_ex": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_spmm_csr_gr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
+    "sgap_config_init": (_int, [_p]),
+    "sgap_spmm_csr_workspace_size": (_i64, [_i64, _i64, _i64, _p]),
+    "sgap_spmm_csr_cfg": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _p]),
     "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
+    "sgap_autotune_csr_cfg": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _i64, _p, _int, _p, _p, _p]),
     "sgap_sddmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
+    "sgap_sddmm_csr_windows": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _int, _int, _int, _p,
+                                      _i64, _p]),
+    "sgap_sddmm_csr_workspace_size": (_i64, [_i64, _i64, _int, _int]),
     "sgap_validate_csr": (_int, [_i64, _i64, _p, _p, _i64, _p, _p]),
     "sgap_ttm_csf": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_mttkrp_csf": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _p]),
@@ -160,8 +167,60 @@ SGAP_TUNE_ROWS_PER_GROUP = 2
 SGAP_TUNE_PERSISTENT = 3
 SGAP_TUNE_NNZ_TILE = 4
 SGAP_TUNE_SDDMM_ROW_CACHE = 5
-SGAP_TUNE_LONG_ROW_MIN = 6
-SGAP_TUNE_PANEL_WINDOW_KB = 7
+
+
+class Config(ctypes.Structure):
+    """Mirror of sgap_config: the point of the design space and the tiling knobs of one call."""
+    _fields_ = [(name, ctypes.c_int) for name in (
+        "schedule", "strategy", "group_size", "reduce_size", "block_size", "tile_cols", "rows_per_group",
+        "xcd_remap", "persistent", "nnz_tile", "wave_rows", "long_row_min", "window_kb", "max_long_rows")]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+def make_config(group_size, strategy, schedule, **knobs) -> Config:
+    """sgap_config with the library's defaults (sgap_config_init) and the named fields set; strategy and
+    schedule by name or number."""
+    c = Config()
+    _check(load().sgap_config_init(ctypes.byref(c)))
+    c.group_size = int(group_size)
+    c.strategy = STRATEGIES.get(strategy, strategy)
+    c.schedule = SCHEDULES.get(schedule, schedule)
+    for k, v in knobs.items():
+        if k not in dict(Config._fields_):
+            raise KeyError(k)
+        setattr(c, k, int(v))
+    return c
+
+
+def sgap_spmm_csr_workspace_size(M, K, N, config: Config) -> int:
+    size = load().sgap_spmm_csr_workspace_size(M, K, N, ctypes.byref(config))
+    if size < 0:
+        raise SgapError(SGAP_ERR_INVALID_ARG, load().sgap_last_error().decode())
+    return size
+
+
+def _workspace_args(workspace):
+    import torch
+
+    if workspace is None:
+        return None, 0
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or workspace.dtype != torch.uint8:
+        raise TypeError("workspace must be a CUDA uint8 tensor")
+    return (workspace.data_ptr() if workspace.numel() else None), workspace.numel()
+
+
+def sgap_spmm_csr_cfg(M, K, N, rowptr, colidx, vals, B, C, config: Config, nnz_hint=None, workspace=None,
+                      stream=None) -> None:
+    """C = A_csr * B at the point and with the tiling `config` names; `workspace` is a CUDA uint8 tensor of
+    at least sgap_spmm_csr_workspace_size bytes when the configuration sets long rows apart."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    ws, ws_bytes = _workspace_args(workspace)
+    _check(load().sgap_spmm_csr_cfg(M, K, N, *ptrs, ctypes.byref(config), int(nnz_hint), ws, ws_bytes,
+                                    _stream_ptr(stream)))
 
 
 def sgap_set_tuning(knob: int, value: int) -> None:
@@ -209,6 +268,36 @@ def sgap_sddmm_csr(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size,
         _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"),
         _dev_ptr(X2T, torch.float32, "X2T"), _dev_ptr(out_vals, torch.float32, "out_vals"),
         int(group_size), int(strategy), int(nnz_hint), _stream_ptr(stream)))
+
+
+def sgap_sddmm_csr_workspace_size(K, J, window_kb=0, max_long_rows=0) -> int:
+    size = load().sgap_sddmm_csr_workspace_size(K, J, int(window_kb), int(max_long_rows))
+    if size < 0:
+        raise SgapError(SGAP_ERR_INVALID_ARG, load().sgap_last_error().decode())
+    return size
+
+
+def sgap_sddmm_csr_windows(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size, strategy, long_row_min,
+                           window_kb=0, max_long_rows=0, workspace=None, nnz_hint=None, stream=None) -> None:
+    """sgap_sddmm_csr with the stored entries of rows of at least long_row_min entries taken by column
+    windows of X2T (see include/sgap.h)."""
+    import torch
+
+    if rowptr.numel() != M + 1:
+        raise ValueError("rowptr must have M+1 entries")
+    if colidx.numel() != vals.numel() or out_vals.numel() != vals.numel():
+        raise ValueError("colidx, vals and out_vals must have the same length")
+    if X1.numel() != M * J or X2T.numel() != K * J:
+        raise ValueError("X1 must hold M*J and X2T must hold K*J elements")
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    ws, ws_bytes = _workspace_args(workspace)
+    _check(load().sgap_sddmm_csr_windows(
+        M, K, J, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+        _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"),
+        _dev_ptr(X2T, torch.float32, "X2T"), _dev_ptr(out_vals, torch.float32, "out_vals"),
+        int(group_size), int(strategy), int(nnz_hint), int(long_row_min), int(window_kb), int(max_long_rows),
+        ws, ws_bytes, _stream_ptr(stream)))
 
 
 def sgap_ttm_csf(F, K, L, eptr, eidx, vals, X1, Yf, group_size, strategy, schedule, nnz_hint=None,
@@ -276,6 +365,31 @@ def sgap_autotune_csr(M, K, N, rowptr, colidx, vals, B, C, nnz_hint=None, reps=3
                                     ctypes.cast(table, ctypes.c_void_p), ctypes.cast(ctypes.pointer(best), ctypes.c_void_p),
                                     _stream_ptr(stream)))
     return best, list(table)
+
+
+class TunedPoint(ctypes.Structure):
+    """Mirror of sgap_tuned_point."""
+    _fields_ = [("config", Config), ("ms", ctypes.c_float)]
+
+
+SGAP_MAX_TUNED_POINTS = 96
+
+
+def sgap_autotune_csr_cfg(M, K, N, rowptr, colidx, vals, B, C, nnz_hint=None, reps=3, workspace=None, stream=None):
+    """Rate the whole configuration space on these operands (blocking).  Returns (best, table): the
+    fastest TunedPoint and the list of all rated ones."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    ws, ws_bytes = _workspace_args(workspace)
+    table = (TunedPoint * SGAP_MAX_TUNED_POINTS)()
+    best = TunedPoint()
+    count = ctypes.c_int(0)
+    _check(load().sgap_autotune_csr_cfg(M, K, N, *ptrs, int(nnz_hint), int(reps), ws, ws_bytes,
+                                        ctypes.cast(table, ctypes.c_void_p), SGAP_MAX_TUNED_POINTS,
+                                        ctypes.cast(ctypes.pointer(count), ctypes.c_void_p),
+                                        ctypes.cast(ctypes.pointer(best), ctypes.c_void_p), _stream_ptr(stream)))
+    return best, list(table)[:min(count.value, SGAP_MAX_TUNED_POINTS)]
 
 
 def sgap_debug_group_partial_reduce(inp, out, group_size, reduce_size, lanes_per_row, stream=None) -> None:

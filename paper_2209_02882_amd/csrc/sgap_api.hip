@@ -1,9 +1,11 @@
 // C ABI of the library: argument validation, choice of kernel instance,
 // launches on the caller's stream.  See include/sgap.h for the contract.
 #include "../../include/sgap.h"
+#include "../../include/sgap_debug.h"
 
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <utility>
 #include <vector>
 
@@ -149,8 +151,6 @@ int g_xcd_remap = -1;  // -1 auto (on), 0 off, 1 on
 int g_rows_per_slot = 0;
 int g_sddmm_row_cache = 1;  // SDDMM parallel: keep rows of X1 in registers where the shape allows
 int g_nnz_tile = 0;    // nnz-balanced serial: forced tile size, 0 = automatic
-int g_long_row_min = 0;     // row-split: rows of at least this many entries go window by window; 0 = off
-int g_panel_window_kb = 0;  // bytes of B per column window in KiB; 0 = automatic (2 MiB)
 int g_persistent = 0;  // row-split: one workgroup per item keeps the rows in flight on a die close together
 
 bool g_profile = false;
@@ -181,6 +181,9 @@ int pow2_ceil_capped(int64_t v, int cap)
 constexpr int kXcds = 8;            // accelerator dies, each with its own L2
 constexpr int64_t kMaxEntries = 2147483647LL - 65535;  // 32-bit positions with room for a tile past the end
 constexpr int kAutoTileCols = 128;  // 512 bytes of a B row per work item
+constexpr int kAutoWindowKb = 3072;   // KiB of B per column window of the long-rows path: most of a die's 4 MiB L2
+constexpr int kAutoLongRows = 8192;   // capacity of the list of long rows when the caller names none
+constexpr int kMaxLongRows = 1 << 20;
 
 int compute_units()
 {
@@ -195,26 +198,84 @@ int compute_units()
     return cus;
 }
 
-int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
-              const float* B, float* C, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream,
-              int reduce_size = 0)
+// The library's choice for every knob a caller may leave open, with the process-wide overrides of
+// sgap_set_tuning filled in: what the entry points without a configuration argument run with.
+sgap_config config_from_globals(int schedule, int strategy, int group_size, int reduce_size)
 {
-    // reduce_size = 0: the group reduces as a whole; 1 <= reduce_size < group_size
-    // (row-split, parallel strategy only): sub-groups merged with atomics
+    sgap_config c;
+    std::memset(&c, 0, sizeof(c));
+    c.schedule = schedule;
+    c.strategy = strategy;
+    c.group_size = group_size;
+    c.reduce_size = reduce_size;
+    c.tile_cols = g_tile_cols;
+    c.rows_per_group = g_rows_per_slot;
+    c.xcd_remap = g_xcd_remap;
+    c.persistent = g_persistent;
+    c.nnz_tile = g_nnz_tile;
+    return c;
+}
+
+int check_config(const sgap_config& c)
+{
+    if (!is_pow2_group(c.group_size)) return fail(SGAP_ERR_INVALID_ARG, "group_size must be 1,2,4,8,16,32 or 64");
+    if (c.strategy != SGAP_REDUCE_PARALLEL && c.strategy != SGAP_REDUCE_SERIAL)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
+    if (c.schedule != SGAP_SCHED_ROW_SPLIT && c.schedule != SGAP_SCHED_NNZ_BALANCED)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
+    if (c.reduce_size != 0 && (!is_pow2_group(c.reduce_size) || c.reduce_size > c.group_size))
+        return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
+    if (c.reduce_size != 0 && c.reduce_size != c.group_size &&
+        (c.schedule != SGAP_SCHED_ROW_SPLIT || c.strategy != SGAP_REDUCE_PARALLEL))
+        return fail(SGAP_ERR_INVALID_ARG, "reduce_size < group_size needs the row-split schedule and the parallel strategy");
+    if (c.block_size != 0 && c.block_size != 128 && c.block_size != 256 && c.block_size != 512)
+        return fail(SGAP_ERR_INVALID_ARG, "block_size must be 0, 128, 256 or 512");
+    if (c.tile_cols < 0) return fail(SGAP_ERR_INVALID_ARG, "tile_cols must be >= 0");
+    if (c.rows_per_group < 0 || c.rows_per_group > 65536)
+        return fail(SGAP_ERR_INVALID_ARG, "rows_per_group out of range");
+    if (c.xcd_remap < -1 || c.xcd_remap > 1) return fail(SGAP_ERR_INVALID_ARG, "xcd_remap must be -1, 0 or 1");
+    if (c.nnz_tile != 0 && c.nnz_tile != 256 && c.nnz_tile != 512 && c.nnz_tile != 1024 && c.nnz_tile != 2048)
+        return fail(SGAP_ERR_INVALID_ARG, "nnz_tile must be 0, 256, 512, 1024 or 2048");
+    if (c.long_row_min < 0) return fail(SGAP_ERR_INVALID_ARG, "long_row_min must be >= 0");
+    if (c.window_kb < 0 || c.window_kb > (1 << 20)) return fail(SGAP_ERR_INVALID_ARG, "window_kb out of range");
+    if (c.max_long_rows < 0 || c.max_long_rows > kMaxLongRows)
+        return fail(SGAP_ERR_INVALID_ARG, "max_long_rows must be between 0 and 1,048,576");
+    if (c.wave_rows < -1 || c.wave_rows > 1) return fail(SGAP_ERR_INVALID_ARG, "wave_rows must be -1, 0 or 1");
+    return SGAP_OK;
+}
+
+int widest_vec(int64_t N, const void* p, const void* q)
+{
+    const uintptr_t align_bits = reinterpret_cast<uintptr_t>(p) | reinterpret_cast<uintptr_t>(q);
+    if (N % 4 == 0 && (align_bits & 15) == 0) return 4;
+    if (N % 2 == 0 && (align_bits & 7) == 0) return 2;
+    return 1;
+}
+
+// does this call take its long rows by column windows?
+bool windows_apply(const sgap_config& c, int vec)
+{
+    const bool whole_group = c.reduce_size == 0 || c.reduce_size == c.group_size;
+    return c.long_row_min > 0 && c.schedule == SGAP_SCHED_ROW_SPLIT && whole_group && vec == 4;
+}
+
+int64_t window_bytes_of(const sgap_config& c) { return (int64_t)(c.window_kb > 0 ? c.window_kb : kAutoWindowKb) * 1024; }
+int64_t long_rows_of(const sgap_config& c) { return c.max_long_rows > 0 ? c.max_long_rows : kAutoLongRows; }
+
+int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+              const float* B, float* C, const sgap_config& c, int64_t nnz_hint, void* workspace,
+              int64_t workspace_bytes, void* stream)
+{
     using namespace sgap;
     if (M < 0 || K < 0 || N < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
     if (M > 2147483646LL || N > 2147483647LL || K > 2147483647LL)
         return fail(SGAP_ERR_INVALID_ARG, "dimension exceeds int32 index range");
-    if (!is_pow2_group(group_size)) return fail(SGAP_ERR_INVALID_ARG, "group_size must be 1,2,4,8,16,32 or 64");
-    if (strategy != SGAP_REDUCE_PARALLEL && strategy != SGAP_REDUCE_SERIAL)
-        return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
-    if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
-        return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
+    if (const int st = check_config(c)) return st;
     if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
     if (nnz_hint > kMaxEntries) return fail(SGAP_ERR_INVALID_ARG, "more stored entries than 2^31 - 65536");
-    if (reduce_size != 0 && (!is_pow2_group(reduce_size) || reduce_size > group_size))
-        return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
-    if (reduce_size == group_size) reduce_size = 0;
+    if (workspace_bytes < 0) return fail(SGAP_ERR_INVALID_ARG, "workspace_bytes must be >= 0");
+    const int group_size = c.group_size;
+    const int reduce_size = c.reduce_size == group_size ? 0 : c.reduce_size;
     if (M == 0 || N == 0) return SGAP_OK;
     if (!rowptr || !C) return fail(SGAP_ERR_INVALID_ARG, "rowptr and C must not be null");
     if (K > 0 && !B) return fail(SGAP_ERR_INVALID_ARG, "B must not be null when K > 0");
@@ -222,11 +283,16 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
         return fail(SGAP_ERR_INVALID_ARG, "colidx and vals must not be null when A has entries");
 
     // columns per lane (coarsening c): widest vector the shape and alignment allow
-    const uintptr_t align_bits = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
-    int vec = 1;
-    if (N % 4 == 0 && (align_bits & 15) == 0) vec = 4;
-    else if (N % 2 == 0 && (align_bits & 7) == 0) vec = 2;
+    const int vec = widest_vec(N, B, C);
     const int64_t chunks = (N + vec - 1) / vec;
+    const bool windows = windows_apply(c, vec) && K > 0;
+    if (windows) {
+        const int64_t need = spmm_panels_workspace_bytes(K, N, window_bytes_of(c), long_rows_of(c));
+        if (!workspace || workspace_bytes < need)
+            return fail(SGAP_ERR_INVALID_ARG, "long_row_min > 0 needs a workspace of sgap_spmm_csr_workspace_size bytes");
+        if (reinterpret_cast<uintptr_t>(workspace) & 255)
+            return fail(SGAP_ERR_INVALID_ARG, "the workspace must be 256-byte aligned");
+    }
 
     SpmmArgs a;
     a.M = M; a.K = K; a.N = N;
@@ -235,28 +301,31 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
     a.log2_group = ilog2(group_size);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
+    // while profiling is on, a pair of events brackets everything the call enqueues
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     hipError_t err = hipSuccess;
     auto mark = [&](hipEvent_t& ev) {
         if (g_profile && hipEventCreate(&ev) == hipSuccess) hipEventRecord(ev, s);
     };
+    mark(ev0);
 
-    if (schedule == SGAP_SCHED_ROW_SPLIT) {
-        const int xcds = g_xcd_remap == 0 ? 1 : kXcds;
+    const bool par = c.strategy == SGAP_REDUCE_PARALLEL;
+    if (c.schedule == SGAP_SCHED_ROW_SPLIT) {
+        const int xcds = c.xcd_remap == 0 ? 1 : kXcds;
         const int cus = compute_units();
-        const bool par = strategy == SGAP_REDUCE_PARALLEL;
+        const int block = c.block_size > 0 ? c.block_size : kBlock;
         const int g = par ? group_size : 1;  // lanes per row
         const double avg_row = nnz_hint > 0 ? (double)nnz_hint / (double)M : 16.0;
         // Column tile: how many columns of B/C one work item covers.
-        int64_t tile_cols = g_tile_cols > 0 ? g_tile_cols : kAutoTileCols;
+        int64_t tile_cols = c.tile_cols > 0 ? c.tile_cols : kAutoTileCols;
         if (tile_cols > N) tile_cols = N;
         tile_cols = (tile_cols + vec - 1) / vec * vec;
         const int lc = pow2_ceil_capped(tile_cols / vec, 64 / g);
-        int rows_per_slot = par ? g_rows_per_slot : group_size;
+        int rows_per_slot = par ? c.rows_per_group : group_size;
         if (rows_per_slot <= 0) {
             // rows a group works through per item: enough stored entries per
             // workgroup to amortise staging, few enough that neighbouring rows stay in flight together
-            const int slots = 256 / (g * lc);
+            const int slots = block / (g * lc);
             rows_per_slot = (int)(432.0 / (avg_row * slots) + 0.5);
             if (rows_per_slot < 1) rows_per_slot = 1;
             if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
@@ -264,40 +333,145 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
         if (reduce_size != 0) {
             // every row receives atomic adds
             err = launch_nnz_zero_rows(a, vec, -1, s);
-            if (err == hipSuccess) {
-                mark(ev0);
+            if (err == hipSuccess)
                 err = launch_row_split_partial(a, g, reduce_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus,
-                                               g_persistent != 0, s);
-            }
-        } else if (g_long_row_min > 0 && vec == 4) {
-            mark(ev0);
+                                               c.persistent != 0, block, s);
+        } else if (windows) {
             err = launch_row_split_panels(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus,
-                                          g_persistent != 0, g_long_row_min,
-                                          (int64_t)(g_panel_window_kb > 0 ? g_panel_window_kb : 2048) * 1024, s);
+                                          c.persistent != 0, block, c.long_row_min, window_bytes_of(c), workspace,
+                                          long_rows_of(c), s);
+        } else if (c.wave_rows == 1 && !par && N >= 48) {
+            // one wavefront per group_size consecutive rows, all 64 lanes on column chunks
+            const int vw = N > 128 ? vec : N > 64 ? (vec < 2 ? vec : 2) : 1;
+            err = launch_wave_rows(a, vw, group_size > 63 ? 63 : group_size, xcds, nullptr, s);
         } else {
-            mark(ev0);
             // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
             // own consecutive rows by definition
-            err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, g_persistent != 0,
-                                   s);
+            err = launch_row_split(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus, c.persistent != 0,
+                                   block, s);
         }
     } else {
-        const bool par = strategy == SGAP_REDUCE_PARALLEL;
         const int lc = pow2_ceil_capped(chunks, par ? 64 / group_size : 64);
         const NnzPlan plan = par ? plan_nnz_parallel(group_size, lc, vec)
-                                 : plan_nnz_serial(group_size, lc, vec, nnz_hint, compute_units(), g_nnz_tile);
+                                 : plan_nnz_serial(group_size, lc, vec, nnz_hint, compute_units(), c.nnz_tile);
         err = launch_nnz_zero_rows(a, vec, plan.merge_log2, s);
-        if (err == hipSuccess) {
-            mark(ev0);
+        if (err == hipSuccess)
             err = par ? launch_nnz_parallel(a, lc, vec, compute_units(), nnz_hint, s)
                       : launch_nnz_serial(a, lc, vec, plan, compute_units(), nnz_hint, s);
-        }
     }
     if (ev0) {
         mark(ev1);
         if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);
     }
     if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
+// The tuner behind sgap_autotune_csr and sgap_autotune_csr_cfg: times candidate configurations on the
+// caller's operands with events on the caller's stream.  wide = false: the 28 (group size, strategy, schedule)
+// points; wide = true: also the points with the reduction narrower than the tiling, the long rows by column
+// windows (when the workspace is large enough) and, around the fastest point found, the tiling knobs of
+// Section 7.2's space <groupSz, blockSz, tileSz, workerDimR>.
+int tune_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+              const float* B, float* C, int64_t nnz_hint, int reps, void* workspace, int64_t workspace_bytes, bool wide,
+              sgap_tuned_point* table, int capacity, int* count, sgap_tuned_point* best, void* stream)
+{
+    if (reps < 1) return fail(SGAP_ERR_INVALID_ARG, "reps must be >= 1");
+    if (M <= 0 || N <= 0) return fail(SGAP_ERR_INVALID_ARG, "nothing to time: M and N must be positive");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) hipEventDestroy(e0);
+        return fail(SGAP_ERR_HIP, "could not create timing events");
+    }
+    int status = SGAP_OK;
+    // one timed run of a configuration; < 0 on error
+    auto timed = [&](const sgap_config& c) -> float {
+        float ms = -1.0f;
+        if (hipEventRecord(e0, s) != hipSuccess) status = fail(SGAP_ERR_HIP, "event record failed");
+        if (status == SGAP_OK)
+            status = spmm_impl(M, K, N, rowptr, colidx, vals, B, C, c, nnz_hint, workspace, workspace_bytes, stream);
+        if (status == SGAP_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                                  hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            status = fail(SGAP_ERR_HIP, "could not time a launch");
+        return status == SGAP_OK ? ms : -1.0f;
+    };
+    sgap_tuned_point fastest;
+    fastest.ms = -1.0f;
+    int n = 0;
+    // a configuration runs once, timed, as a warm-up and, unless that run was more than 4 times slower than the
+    // best so far, `reps` more times; its time is the minimum
+    auto rate = [&](const sgap_config& c) {
+        if (status != SGAP_OK) return;
+        // a window size the caller's workspace does not cover is not a candidate
+        if (windows_apply(c, widest_vec(N, B, C)) && K > 0 &&
+            (!workspace || workspace_bytes < sgap::spmm_panels_workspace_bytes(K, N, window_bytes_of(c), long_rows_of(c))))
+            return;
+        sgap_tuned_point pt;
+        pt.config = c;
+        pt.ms = timed(c);
+        const bool hopeless = fastest.ms > 0.0f && pt.ms > 4.0f * fastest.ms;
+        for (int r = 0; r < reps && !hopeless && status == SGAP_OK; ++r) {
+            const float ms = timed(c);
+            if (ms < pt.ms) pt.ms = ms;
+        }
+        if (status != SGAP_OK) return;
+        if (table && n < capacity) table[n] = pt;
+        ++n;
+        if (fastest.ms < 0.0f || pt.ms < fastest.ms) fastest = pt;
+    };
+    for (int schedule : {SGAP_SCHED_ROW_SPLIT, SGAP_SCHED_NNZ_BALANCED})
+        for (int strategy : {SGAP_REDUCE_PARALLEL, SGAP_REDUCE_SERIAL})
+            for (int group = 1; group <= 64; group *= 2) rate(config_from_globals(schedule, strategy, group, 0));
+    if (wide) {
+        // {<1/g row, c col>, r} with r < g (Table 1's experiment)
+        for (int group = 2; group <= 64; group *= 2)
+            for (int r = 1; r < group; r *= 2)
+                rate(config_from_globals(SGAP_SCHED_ROW_SPLIT, SGAP_REDUCE_PARALLEL, group, r));
+        // long rows by column windows, if the caller brought working memory for the default list and window
+        sgap_config probe = config_from_globals(SGAP_SCHED_ROW_SPLIT, SGAP_REDUCE_SERIAL, 1, 0);
+        probe.long_row_min = 1024;
+        const int vec = widest_vec(N, B, C);
+        if (workspace && K > 0 && windows_apply(probe, vec) &&
+            workspace_bytes >= sgap::spmm_panels_workspace_bytes(K, N, window_bytes_of(probe), long_rows_of(probe)) &&
+            (reinterpret_cast<uintptr_t>(workspace) & 255) == 0) {
+            for (int strategy : {SGAP_REDUCE_SERIAL, SGAP_REDUCE_PARALLEL})
+                for (int group = 1; group <= 8; group *= 2)
+                    for (int min_len : {512, 2048}) {
+                        sgap_config c = config_from_globals(SGAP_SCHED_ROW_SPLIT, strategy, group, 0);
+                        c.long_row_min = min_len;
+                        rate(c);
+                    }
+        }
+        // around the fastest point: workgroup size, column tile, rows per group (row-split); tile of entries
+        // (nnz-balanced serial); one knob at a time, keeping what helps
+        if (status == SGAP_OK) {
+            auto try_values = [&](int sgap_config::*knob, std::initializer_list<int> values) {
+                const sgap_config base = fastest.config;
+                for (int v : values) {
+                    if (base.*knob == v) continue;
+                    sgap_config c = base;
+                    c.*knob = v;
+                    rate(c);
+                }
+            };
+            if (fastest.config.schedule == SGAP_SCHED_ROW_SPLIT) {
+                try_values(&sgap_config::block_size, {128, 512});
+                try_values(&sgap_config::tile_cols, {32, 64, 256});
+                if (fastest.config.strategy == SGAP_REDUCE_PARALLEL) try_values(&sgap_config::rows_per_group, {1, 2, 4, 8, 16});
+                if (fastest.config.long_row_min > 0) try_values(&sgap_config::window_kb, {2048, 4096});
+            } else if (fastest.config.strategy == SGAP_REDUCE_SERIAL) {
+                try_values(&sgap_config::nnz_tile, {512, 1024, 2048});
+            }
+        }
+    }
+    // leave the fastest point's result in C
+    if (status == SGAP_OK) timed(fastest.config);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (status != SGAP_OK) return status;
+    *count = n;
+    *best = fastest;
     return SGAP_OK;
 }
 
@@ -318,14 +492,16 @@ int sgap_get_schedule(void) { return g_schedule; }
 int sgap_spmm_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx, const float* vals,
                   const float* B, float* C, int group_size, int strategy, void* stream)
 {
-    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, g_schedule, -1, stream);
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, config_from_globals(g_schedule, strategy, group_size, 0), -1,
+                     nullptr, 0, stream);
 }
 
 int sgap_spmm_csr_ex(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
                      const float* vals, const float* B, float* C, int group_size, int strategy, int schedule,
                      int64_t nnz_hint, void* stream)
 {
-    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, strategy, schedule, nnz_hint, stream);
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, config_from_globals(schedule, strategy, group_size, 0),
+                     nnz_hint, nullptr, 0, stream);
 }
 
 int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
@@ -333,13 +509,47 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, con
                      void* stream)
 {
     if (reduce_size < 1) return fail(SGAP_ERR_INVALID_ARG, "reduce_size must be a power of two, 1 <= reduce_size <= group_size");
-    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, group_size, SGAP_REDUCE_PARALLEL, SGAP_SCHED_ROW_SPLIT,
-                     nnz_hint, stream, reduce_size);
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C,
+                     config_from_globals(SGAP_SCHED_ROW_SPLIT, SGAP_REDUCE_PARALLEL, group_size, reduce_size), nnz_hint,
+                     nullptr, 0, stream);
 }
 
-int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx, const float* vals,
-                   const float* X1, const float* X2T, float* out_vals, int group_size, int strategy, int64_t nnz_hint,
-                   void* stream)
+int sgap_config_init(sgap_config* config)
+{
+    if (!config) return fail(SGAP_ERR_INVALID_ARG, "config must not be null");
+    std::memset(config, 0, sizeof(*config));
+    config->schedule = SGAP_SCHED_ROW_SPLIT;
+    config->strategy = SGAP_REDUCE_PARALLEL;
+    config->group_size = 8;
+    config->xcd_remap = -1;
+    return SGAP_OK;
+}
+
+int64_t sgap_spmm_csr_workspace_size(int64_t M, int64_t K, int64_t N, const sgap_config* config)
+{
+    if (!config || M < 0 || K < 0 || N < 0) {
+        fail(SGAP_ERR_INVALID_ARG, "bad arguments");
+        return -1;
+    }
+    if (check_config(*config) != SGAP_OK) return -1;
+    // (the vector width is not known without the operands: sized as if the window path applied)
+    if (config->long_row_min == 0 || config->schedule != SGAP_SCHED_ROW_SPLIT || N % 4 != 0 || K == 0 || N == 0) return 0;
+    if (config->reduce_size != 0 && config->reduce_size != config->group_size) return 0;
+    return sgap::spmm_panels_workspace_bytes(K, N, window_bytes_of(*config), long_rows_of(*config));
+}
+
+int sgap_spmm_csr_cfg(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                      const float* vals, const float* B, float* C, const sgap_config* config, int64_t nnz_hint,
+                      void* workspace, int64_t workspace_bytes, void* stream)
+{
+    if (!config) return fail(SGAP_ERR_INVALID_ARG, "config must not be null");
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, *config, nnz_hint, workspace, workspace_bytes, stream);
+}
+
+static int sddmm_impl(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx,
+                      const float* vals, const float* X1, const float* X2T, float* out_vals, int group_size,
+                      int strategy, int64_t nnz_hint, int long_row_min, int window_kb, int max_long_rows,
+                      void* workspace, int64_t workspace_bytes, void* stream)
 {
     using namespace sgap;
     if (M < 0 || K < 0 || J < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
@@ -350,6 +560,9 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
         return fail(SGAP_ERR_INVALID_ARG, "unknown strategy");
     if (nnz_hint < -1) return fail(SGAP_ERR_INVALID_ARG, "nnz_hint must be -1 or a count");
     if (nnz_hint > kMaxEntries) return fail(SGAP_ERR_INVALID_ARG, "more stored entries than 2^31 - 65536");
+    if (long_row_min < 0 || window_kb < 0 || window_kb > (1 << 20) || max_long_rows < 0 || max_long_rows > kMaxLongRows ||
+        workspace_bytes < 0)
+        return fail(SGAP_ERR_INVALID_ARG, "bad long-row arguments");
     if (M == 0 || nnz_hint == 0) return SGAP_OK;
     if (!rowptr) return fail(SGAP_ERR_INVALID_ARG, "rowptr must not be null");
     if (!colidx || !vals || !out_vals) {
@@ -377,11 +590,19 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     mark(ev0);
     const bool par = strategy == SGAP_REDUCE_PARALLEL;
     hipError_t err;
-    if (g_long_row_min > 0 && vec == 4 && J >= 32 && J <= 256)
+    if (long_row_min > 0 && vec == 4 && J >= 32 && J <= 256 && K > 0) {
+        const int64_t window_bytes = (int64_t)(window_kb > 0 ? window_kb : 2048) * 1024;
+        const int64_t cap = max_long_rows > 0 ? max_long_rows : kAutoLongRows;
+        if (!workspace || workspace_bytes < sddmm_panels_workspace_bytes(K, J, window_bytes, cap) ||
+            (reinterpret_cast<uintptr_t>(workspace) & 255)) {
+            if (ev0) hipEventDestroy(ev0);
+            return fail(SGAP_ERR_INVALID_ARG,
+                        "long_row_min > 0 needs a 256-byte aligned workspace of sgap_sddmm_csr_workspace_size bytes");
+        }
         err = launch_sddmm_panels(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size,
-                                  g_xcd_remap == 0 ? 1 : kXcds, compute_units(), nnz_hint, g_long_row_min,
-                                  (int64_t)(g_panel_window_kb > 0 ? g_panel_window_kb : 2048) * 1024, s);
-    else
+                                  g_xcd_remap == 0 ? 1 : kXcds, compute_units(), nnz_hint, long_row_min, window_bytes,
+                                  workspace, cap, s);
+    } else
         err = launch_sddmm(a, X1, out_vals, par ? group_size : 1, par ? 0 : group_size, vec, g_sddmm_row_cache != 0,
                            compute_units(), nnz_hint, s);
     if (ev0) {
@@ -392,12 +613,41 @@ int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const
     return SGAP_OK;
 }
 
+int sgap_sddmm_csr(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                   const float* X1, const float* X2T, float* out_vals, int group_size, int strategy, int64_t nnz_hint,
+                   void* stream)
+{
+    return sddmm_impl(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size, strategy, nnz_hint, 0, 0, 0, nullptr,
+                      0, stream);
+}
+
+int sgap_sddmm_csr_windows(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx,
+                           const float* vals, const float* X1, const float* X2T, float* out_vals, int group_size,
+                           int strategy, int64_t nnz_hint, int long_row_min, int window_kb, int max_long_rows,
+                           void* workspace, int64_t workspace_bytes, void* stream)
+{
+    return sddmm_impl(M, K, J, rowptr, colidx, vals, X1, X2T, out_vals, group_size, strategy, nnz_hint, long_row_min,
+                      window_kb, max_long_rows, workspace, workspace_bytes, stream);
+}
+
+int64_t sgap_sddmm_csr_workspace_size(int64_t K, int64_t J, int window_kb, int max_long_rows)
+{
+    if (K < 0 || J < 0 || window_kb < 0 || window_kb > (1 << 20) || max_long_rows < 0 || max_long_rows > kMaxLongRows) {
+        fail(SGAP_ERR_INVALID_ARG, "bad arguments");
+        return -1;
+    }
+    if (K == 0 || J % 4 != 0 || J < 32 || J > 256) return 0;  // the window path does not apply
+    return sgap::sddmm_panels_workspace_bytes(K, J, (int64_t)(window_kb > 0 ? window_kb : 2048) * 1024,
+                                              max_long_rows > 0 ? max_long_rows : kAutoLongRows);
+}
+
 int sgap_ttm_csf(int64_t F, int64_t K, int64_t L, const int32_t* eptr, const int32_t* eidx, const float* vals,
                  const float* X1, float* Yf, int group_size, int strategy, int schedule, int64_t nnz_hint,
                  void* stream)
 {
     // the reduction over the entries of a fiber is the SpMM reduction over the entries of a row
-    return spmm_impl(F, K, L, eptr, eidx, vals, X1, Yf, group_size, strategy, schedule, nnz_hint, stream);
+    return spmm_impl(F, K, L, eptr, eidx, vals, X1, Yf, config_from_globals(schedule, strategy, group_size, 0), nnz_hint,
+                     nullptr, 0, stream);
 }
 
 int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* fptr, const int32_t* fidx,
@@ -449,52 +699,31 @@ int sgap_autotune_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, co
                       sgap_point_time* best, void* stream)
 {
     if (!best) return fail(SGAP_ERR_INVALID_ARG, "best must not be null");
-    if (reps < 1) return fail(SGAP_ERR_INVALID_ARG, "reps must be >= 1");
-    if (M <= 0 || N <= 0) return fail(SGAP_ERR_INVALID_ARG, "nothing to time: M and N must be positive");
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
-        if (e0) hipEventDestroy(e0);
-        return fail(SGAP_ERR_HIP, "could not create timing events");
-    }
-    int status = SGAP_OK;
-    // one timed run of a point; < 0 on error
-    auto timed = [&](const sgap_point_time& pt) -> float {
-        float ms = -1.0f;
-        if (hipEventRecord(e0, s) != hipSuccess) status = fail(SGAP_ERR_HIP, "event record failed");
-        if (status == SGAP_OK)
-            status = spmm_impl(M, K, N, rowptr, colidx, vals, B, C, pt.group_size, pt.strategy, pt.schedule, nnz_hint,
-                               stream);
-        if (status == SGAP_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-                                  hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
-            status = fail(SGAP_ERR_HIP, "could not time a launch");
-        return status == SGAP_OK ? ms : -1.0f;
-    };
-    sgap_point_time fastest = {0, 0, 0, -1.0f};
-    int idx = 0;
-    for (int schedule : {SGAP_SCHED_ROW_SPLIT, SGAP_SCHED_NNZ_BALANCED}) {
-        for (int strategy : {SGAP_REDUCE_PARALLEL, SGAP_REDUCE_SERIAL}) {
-            for (int group = 1; group <= 64 && status == SGAP_OK; group *= 2, ++idx) {
-                sgap_point_time pt = {group, strategy, schedule, 0.0f};
-                pt.ms = timed(pt);
-                const bool hopeless = fastest.ms > 0.0f && pt.ms > 4.0f * fastest.ms;
-                for (int r = 0; r < reps && !hopeless && status == SGAP_OK; ++r) {
-                    const float ms = timed(pt);
-                    if (ms < pt.ms) pt.ms = ms;
-                }
-                if (status != SGAP_OK) break;
-                if (table) table[idx] = pt;
-                if (fastest.ms < 0.0f || pt.ms < fastest.ms) fastest = pt;
-            }
-        }
-    }
-    // leave the fastest point's result in C
-    if (status == SGAP_OK) timed(fastest);
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    std::vector<sgap_tuned_point> points(SGAP_NUM_POINTS);
+    sgap_tuned_point fastest;
+    int count = 0;
+    const int status = tune_impl(M, K, N, rowptr, colidx, vals, B, C, nnz_hint, reps, nullptr, 0, false, points.data(),
+                                 SGAP_NUM_POINTS, &count, &fastest, stream);
     if (status != SGAP_OK) return status;
-    *best = fastest;
+    for (int i = 0; i < count && table; ++i)
+        table[i] = {points[i].config.group_size, points[i].config.strategy, points[i].config.schedule, points[i].ms};
+    *best = {fastest.config.group_size, fastest.config.strategy, fastest.config.schedule, fastest.ms};
     return SGAP_OK;
+}
+
+int sgap_autotune_csr_cfg(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                          const float* vals, const float* B, float* C, int64_t nnz_hint, int reps, void* workspace,
+                          int64_t workspace_bytes, sgap_tuned_point* table, int capacity, int* count,
+                          sgap_tuned_point* best, void* stream)
+{
+    if (!best) return fail(SGAP_ERR_INVALID_ARG, "best must not be null");
+    if (capacity < 0 || (capacity > 0 && !table)) return fail(SGAP_ERR_INVALID_ARG, "bad table arguments");
+    if (workspace_bytes < 0) return fail(SGAP_ERR_INVALID_ARG, "workspace_bytes must be >= 0");
+    int n = 0;
+    const int status = tune_impl(M, K, N, rowptr, colidx, vals, B, C, nnz_hint, reps, workspace, workspace_bytes, true,
+                                 table, capacity, &n, best, stream);
+    if (count) *count = n;
+    return status;
 }
 
 const char* sgap_status_string(int status)
@@ -533,14 +762,6 @@ int sgap_set_tuning(int knob, int value)
             if (value != 0 && value != 256 && value != 512 && value != 1024 && value != 2048)
                 return fail(SGAP_ERR_INVALID_ARG, "nnz tile must be 0, 256, 512, 1024 or 2048");
             g_nnz_tile = value;
-            return SGAP_OK;
-        case SGAP_TUNE_LONG_ROW_MIN:
-            if (value < 0) return fail(SGAP_ERR_INVALID_ARG, "long row threshold must be >= 0");
-            g_long_row_min = value;
-            return SGAP_OK;
-        case SGAP_TUNE_PANEL_WINDOW_KB:
-            if (value < 0 || value > (1 << 20)) return fail(SGAP_ERR_INVALID_ARG, "window size out of range");
-            g_panel_window_kb = value;
             return SGAP_OK;
         case SGAP_TUNE_ROWS_PER_GROUP:
             if (value < 0 || value > 65536) return fail(SGAP_ERR_INVALID_ARG, "rows per group out of range");

@@ -171,18 +171,28 @@ NnzPlan plan_nnz_parallel(int group, int lc, int vec);
 // block when `interleave` is set), tile_cols = columns per work item, xcds = 8
 // or 1, compute_units = CUs of the device; persistent = launch only as many
 // workgroups as fit the chip and let each walk several items (else one
-// workgroup per item).
+// workgroup per item); block = threads per workgroup (128, 256 or 512).
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                            int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
+                            int tile_cols, int xcds, int compute_units, bool persistent, int block, hipStream_t s);
 // the same with g lanes per row reducing in sub-groups of r < g lanes whose sums
 // are merged with atomics; C must have been zeroed (launch_nnz_zero_rows, -1)
 hipError_t launch_row_split_partial(const SpmmArgs& a, int g, int r, int lc, int vec, int rows_per_slot,
-                                    int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s);
+                                    int tile_cols, int xcds, int compute_units, bool persistent, int block,
+                                    hipStream_t s);
 // the row-split launch with rows of at least min_len stored entries taken out and
-// produced window by window of about window_bytes of B (sgap_panels.hip); vec must be 4
+// produced window by window of about window_bytes of B (sgap_panels.hip); vec must be 4;
+// workspace = device memory of spmm_panels_workspace_bytes(K, N, window_bytes, cap) bytes
+// for a list of up to cap long rows (more long rows than that: the row-split kernel takes every row)
 hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                                   int tile_cols, int xcds, int compute_units, bool persistent, int32_t min_len,
-                                   int64_t window_bytes, hipStream_t s);
+                                   int tile_cols, int xcds, int compute_units, bool persistent, int block,
+                                   int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap,
+                                   hipStream_t s);
+int64_t spmm_panels_workspace_bytes(int64_t K, int64_t N, int64_t window_bytes, int64_t cap);
+int64_t sddmm_panels_workspace_bytes(int64_t K, int64_t J, int64_t window_bytes, int64_t cap);
+// row-split, serial strategy, one wavefront per rows_per_wave consecutive rows and 64 * vec columns
+// (sgap_wave_rows.hip); skip = rows another kernel produces, or nullptr
+hipError_t launch_wave_rows(const SpmmArgs& a, int vec, int rows_per_wave, int xcds, const RowSkip* skip,
+                            hipStream_t s);
 // zero the rows of C that receive atomic adds under a merge block of
 // 2^merge_log2 positions, and the rows without entries; merge_log2 = -1: all rows
 hipError_t launch_nnz_zero_rows(const SpmmArgs& a, int vec, int merge_log2, hipStream_t s);
@@ -203,7 +213,7 @@ hipError_t launch_sddmm(const SpmmArgs& a, const float* X1, float* out, int g, i
 // vec must be 4 and 32 <= J <= 256
 hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int xcds,
                                int compute_units, int64_t nnz_hint, int32_t min_len, int64_t window_bytes,
-                               hipStream_t stream);
+                               void* workspace, int64_t cap, hipStream_t stream);
 // the plain SDDMM kernel (no row cache) that leaves the entries of the rows described by `skip` alone
 hipError_t launch_sddmm_skip(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int compute_units,
                              int64_t nnz_hint, const RowSkip& skip, hipStream_t stream);

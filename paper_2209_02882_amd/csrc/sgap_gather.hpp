@@ -14,9 +14,9 @@ struct StagedEntry {
 // Coalesced streaming copy of stored entries [base, base+cnt) into LDS.
 // The caller synchronises.
 __device__ __forceinline__ void stage_entries(const SpmmArgs& a, uint32_t base, uint32_t cnt,
-                                              StagedEntry* __restrict__ s_A)
+                                              StagedEntry* __restrict__ s_A, uint32_t block = kBlock)
 {
-    for (uint32_t q = threadIdx.x; q < cnt; q += kBlock) {
+    for (uint32_t q = threadIdx.x; q < cnt; q += block) {
         StagedEntry e;
         e.col = load_stream(a.colidx + base + q);
         e.val = load_stream(a.vals + base + q);

@@ -21,55 +21,63 @@
 // The row-split kernel then produces all other rows and leaves the long ones
 // alone (`RowSkip`).  Everything is decided on the device, so the call stays
 // asynchronous: the list of long rows and the window pointers live in a
-// file-scope device array (one per GPU, shared by all calls on it: calls that
-// use this path must not overlap on one GPU).  When the matrix has more long
+// workspace of device memory that the caller hands in (sized by
+// panel_workspace_bytes for a list of `cap` rows).  When the matrix has more long
 // rows than the list holds, this path does nothing and the row-split kernel
 // takes every row.
 #include "sgap_common.hpp"
 #include "sgap_lane_ops.hpp"
 #include "sgap_row_split_impl.hpp"
+#include "sgap_uniform.hpp"
 
 namespace sgap {
 
-constexpr int kPanelMaxRows = 8192;    // long rows the list holds
-constexpr int kPanelMaxWindows = 255;  // column windows at most
+constexpr int kPanelMaxWindows = 511;  // column windows at most
+constexpr int kRankMaxRows = 8192;     // lists up to this length are sorted by row length (their lengths fit in LDS)
 
-struct PanelScratch {
-    uint32_t count;     // long rows found (may exceed kPanelMaxRows: then the path is off)
+// The workspace: a header, the list of long rows, the same list sorted by length, and the window pointers.
+struct PanelHeader {
+    uint32_t count;     // long rows found (may exceed the list's capacity: then the path is off)
     uint32_t next[15];  // per die: the next item nobody has taken yet
     uint32_t pad[48];
-    int32_t rows[kPanelMaxRows];
-    // ptr[i * (windows + 1) + w] = first entry of long row i with column >= w * window_rows
-    int32_t ptr[kPanelMaxRows * (kPanelMaxWindows + 1)];
+};
+struct PanelView {
+    PanelHeader* head;
+    int32_t* rows;   // [cap]
+    int32_t* order;  // [cap] the long rows from the longest to the shortest: order[q] indexes rows[]
+    int32_t* ptr;    // [cap * (windows + 1)]: ptr[i * (windows + 1) + w] = first entry of long row i with column >= w * window_rows
+    uint32_t cap;    // rows the list holds
 };
 
-static __device__ __align__(256) PanelScratch g_panel_scratch;
+int64_t panel_workspace_bytes(int64_t cap, int windows)
+{
+    const int64_t ints = 2 * cap + cap * (int64_t)(windows + 1);
+    return (int64_t)sizeof(PanelHeader) + (ints * 4 + 255) / 256 * 256;
+}
 
 namespace {
 
-// device address of this GPU's scratch array (the symbol's name is a host-side stand-in)
-PanelScratch* panel_scratch()
+PanelView panel_view(void* workspace, int64_t cap, int windows)
 {
-    constexpr int kMaxDevices = 64;
-    static PanelScratch* per_device[kMaxDevices] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    if (!per_device[dev]) {
-        void* p = nullptr;
-        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_panel_scratch)) != hipSuccess) return nullptr;
-        per_device[dev] = static_cast<PanelScratch*>(p);
-    }
-    return per_device[dev];
+    PanelView v;
+    char* base = static_cast<char*>(workspace);
+    v.head = reinterpret_cast<PanelHeader*>(base);
+    v.rows = reinterpret_cast<int32_t*>(base + sizeof(PanelHeader));
+    v.order = v.rows + cap;
+    v.ptr = v.order + cap;
+    v.cap = (uint32_t)cap;
+    (void)windows;
+    return v;
 }
 
 }  // namespace
 
-__global__ void panel_reset_kernel(PanelScratch* scr)
+__global__ void panel_reset_kernel(PanelView scr)
 {
-    if (blockIdx.x == 0 && threadIdx.x < 16) (&scr->count)[threadIdx.x] = 0;  // count and next[]
+    if (blockIdx.x == 0 && threadIdx.x < 16) (&scr.head->count)[threadIdx.x] = 0;  // count and next[]
 }
 
-__global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, PanelScratch* scr, int32_t min_len)
+__global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, PanelView scr, int32_t min_len)
 {
     const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const bool is_long = row < a.M && a.rowptr[row + 1] - a.rowptr[row] >= min_len;
@@ -79,27 +87,27 @@ __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, Pan
     if (mask == 0) return;
     const int lane = threadIdx.x % kWave;
     uint32_t base = 0;
-    if (lane == __ffsll((long long)mask) - 1) base = atomicAdd(&scr->count, (uint32_t)__popcll(mask));
+    if (lane == __ffsll((long long)mask) - 1) base = atomicAdd(&scr.head->count, (uint32_t)__popcll(mask));
     base = (uint32_t)__shfl((int)base, __ffsll((long long)mask) - 1, kWave);
     if (is_long) {
         const uint32_t i = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (i < (uint32_t)kPanelMaxRows) scr->rows[i] = (int32_t)row;
+        if (i < scr.cap) scr.rows[i] = (int32_t)row;
     }
 }
 
 // Window pointers of the long rows, and (zero_rows) zeros in their rows of C.
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelScratch* scr, int windows,
+__global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelView scr, int windows,
                                                                 int32_t window_rows, int zero_rows)
 {
-    const uint32_t n = scr->count;
-    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const uint32_t n = scr.head->count;
+    if (n == 0 || n > scr.cap) return;
     const int64_t threads = (int64_t)gridDim.x * kBlock;
     const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int per_row = windows + 1;
     for (int64_t t = tid; t < (int64_t)n * per_row; t += threads) {
         const int i = (int)(t / per_row), w = (int)(t % per_row);
-        const int32_t row = scr->rows[i];
+        const int32_t row = scr.rows[i];
         int32_t lo = a.rowptr[row], hi = a.rowptr[row + 1];
         if (w < windows) {
             // first entry whose column is >= the window's first column.  For any
@@ -114,7 +122,8 @@ __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, Pane
         } else {
             lo = hi;
         }
-        scr->ptr[(int64_t)i * per_row + w] = lo;
+        scr.ptr[(int64_t)i * per_row + w] = lo;
+        if (w == 0) scr.order[i] = i;  // until panel_rank_kernel sorts the list
     }
     if (!zero_rows) return;
     const int64_t chunks = a.N / VEC;  // N % VEC == 0
@@ -123,7 +132,7 @@ __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, Pane
     for (int64_t t = tid; t < (int64_t)n * chunks; t += threads) {
         const int i = (int)(t / chunks);
         const int64_t k = (t % chunks) * VEC;
-        store_vec<VEC>(a.C + (int64_t)scr->rows[i] * a.N + k, z);
+        store_vec<VEC>(a.C + (int64_t)scr.rows[i] * a.N + k, z);
     }
 }
 
@@ -235,12 +244,14 @@ __device__ __forceinline__ void panel_item(const SpmmArgs& a, int32_t p0, int32_
 // item per claim makes the counter the bottleneck (a returning atomic on one
 // address takes about 0.1 us).
 template <int G, int LC, int VEC, bool OFF32>
-__global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, PanelScratch* scr, int windows, int xcds)
+__global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, PanelView scr, int windows, int xcds,
+                                                                 uint32_t below)
 {
+    // below: the kernel runs only for lists of fewer rows (longer lists are panel_owner_kernel's)
     static_assert(G * LC == kWave, "one wavefront per item");
     __shared__ uint32_t s_claim;
-    const uint32_t n = scr->count;
-    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const uint32_t n = scr.head->count;
+    if (n == 0 || n > scr.cap || n >= below) return;
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int per_row = windows + 1;
@@ -248,10 +259,10 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
     const int tiles = (int)((a.N + LC * VEC - 1) / (LC * VEC));
     const int64_t blocks = (int64_t)windows * tiles;
     const int64_t my_blocks = xcd < blocks ? (blocks - xcd + xcds - 1) / xcds : 0;
-    const uint32_t items = (uint32_t)(my_blocks * n);  // host: blocks * kPanelMaxRows < 2^32
+    const uint32_t items = (uint32_t)(my_blocks * n);  // host: blocks * cap < 2^32
     for (;;) {
         __syncthreads();  // everyone has read the previous claim
-        if (threadIdx.x == 0) s_claim = atomicAdd(&scr->next[xcd], (uint32_t)kPanelClaim);
+        if (threadIdx.x == 0) s_claim = atomicAdd(&scr.head->next[xcd], (uint32_t)kPanelClaim);
         __syncthreads();
         const uint32_t claim = s_claim;
         if (claim >= items) break;  // the whole workgroup; the counter only grows, so every workgroup gets here
@@ -262,9 +273,146 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
             const int w = (int)(block / tiles);
             const int64_t k0 = (block % tiles) * (LC * VEC);
             const int i = (int)(it % n);
-            const int32_t p0 = scr->ptr[(int64_t)i * per_row + w];
-            const int32_t p1 = scr->ptr[(int64_t)i * per_row + w + 1];
-            if (p0 < p1) panel_item<G, LC, VEC, OFF32>(a, p0, p1, scr->rows[i], k0, lane);
+            const int32_t p0 = scr.ptr[(int64_t)i * per_row + w];
+            const int32_t p1 = scr.ptr[(int64_t)i * per_row + w + 1];
+            if (p0 < p1) panel_item<G, LC, VEC, OFF32>(a, p0, p1, scr.rows[i], k0, lane);
+        }
+    }
+}
+
+// order[] = the long rows sorted by length, longest first (ties by their place in rows[]).  Every row counts
+// the rows that come before it, sixteen lanes to a row, with all lengths in LDS; a list of more than
+// kRankMaxRows rows keeps the order in which the rows were found (panel_pointers_kernel wrote it): with so
+// many rows every wavefront owns several dozen and their lengths average out.
+constexpr int kRankLanes = 16;
+__global__ __launch_bounds__(kBlock) void panel_rank_kernel(const int32_t* __restrict__ rowptr, PanelView scr)
+{
+    __shared__ int32_t s_len[kRankMaxRows];
+    const uint32_t n = scr.head->count;
+    constexpr uint32_t rows_per_block = kBlock / kRankLanes;
+    if (n == 0 || n > scr.cap || n > (uint32_t)kRankMaxRows || blockIdx.x * rows_per_block >= n) return;
+    for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
+        const int32_t row = scr.rows[i];
+        s_len[i] = rowptr[row + 1] - rowptr[row];
+    }
+    __syncthreads();
+    const uint32_t i = blockIdx.x * rows_per_block + threadIdx.x / kRankLanes;
+    const uint32_t part = threadIdx.x % kRankLanes;
+    const int32_t mine = i < n ? s_len[i] : 0;
+    uint32_t before = 0;
+    for (uint32_t j = part; j < n; j += kRankLanes) {
+        const int32_t other = s_len[j];
+        before += (other > mine || (other == mine && j < i)) ? 1u : 0u;
+    }
+#pragma unroll
+    for (int m = kRankLanes / 2; m >= 1; m /= 2) before += (uint32_t)__shfl_xor((int)before, m, kRankLanes);
+    if (i < n && part == 0) scr.order[before] = (int32_t)i;
+}
+
+constexpr int kOwnerBlock = 1024;  // one workgroup of 16 wavefronts per compute unit
+constexpr int kOwnerWaves = kOwnerBlock / kWave;
+constexpr int kOwnerRows = 10;  // long rows a wavefront owns at a time
+constexpr int kOwnerDepth = 12;  // gathered rows of B in flight per lane
+
+// The same items (window, long row), but every long row has ONE owner wavefront per die, which keeps the row's
+// sums in registers while its die walks its windows and adds them into C once at the end: 8 atomic row pieces per
+// long row instead of one per window.  A die's wavefronts each own up to kOwnerRows rows (more rows: more passes)
+// and take window after window in the same order, so that at any moment they gather from one or two windows,
+// which the die's L2 holds.  Two things keep them in step.  Rows are dealt from the longest to the shortest, back
+// and forth over the wavefronts, so that all have about the same number of entries per window.  And a compute
+// unit runs one workgroup of 16 wavefronts that meet at a barrier after every window: the hardware issues the
+// memory instructions of the oldest wavefronts of a compute unit first, and without the barrier the youngest end
+// up 1.5 times slower and sixteen windows behind (measured), far more than an L2 holds.  Between compute units
+// nothing but their equal shares of the work keeps the pace: they are alike, and each averages over 160 rows.
+// One wavefront per row and 64 lanes on 64 column chunks: the entries are wave-uniform (sgap_uniform.hpp).
+// Runs only when the list holds at least min_rows rows; with fewer, most wavefronts would own nothing and
+// panel_long_rows_kernel (which then runs instead) keeps the whole chip busy.
+template <int VEC, bool OFF32>
+__global__ __launch_bounds__(kOwnerBlock) void panel_owner_kernel(const int32_t* __restrict__ colidx,
+                                                                  const float* __restrict__ vals,
+                                                                  const float* __restrict__ B, float* __restrict__ C,
+                                                                  PanelView scr, int64_t K,
+                                                                  int64_t N, int windows, int xcds, uint32_t min_rows)
+{
+    constexpr int R = kOwnerRows;
+    const uint32_t n = scr.head->count;
+    if (n < min_rows || n > scr.cap) return;
+    const int lane = threadIdx.x % kWave;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t xcd = blockIdx.x % xcds;
+    const uint32_t waves = (gridDim.x / xcds) * kOwnerWaves;  // wavefronts of this die
+    const uint32_t me = (blockIdx.x / xcds) * kOwnerWaves + wave;
+    const uint32_t rounds = (n + waves - 1) / waves;           // rows a wavefront owns in all
+    const int per_row = windows + 1;
+    const int tiles = (int)((N + kWave * VEC - 1) / (kWave * VEC));
+    SpmmArgs a;  // what panel_flush needs
+    a.N = N;
+    a.C = C;
+    for (int tile = 0; tile < tiles; ++tile) {
+        const int64_t k0 = (int64_t)tile * (kWave * VEC);
+        const int64_t k = k0 + (int64_t)lane * VEC;
+        const bool k_ok = k < N;
+        const UniformRows<VEC, OFF32> rows(B, K, N, k_ok ? k : 0);
+        for (uint32_t r0 = 0; r0 < rounds; r0 += R) {
+            // lane l < 2R looks after one number per window: the first (l < R) or the end (l >= R) position
+            // of the entries of row slot l % R in that window; lane l < R also knows the slot's row.
+            // (A wavefront without rows in this pass walks along with nothing to do: it is needed at the barriers.)
+            int64_t my_ptr = -1;
+            int32_t my_row = -1;
+            {
+                const uint32_t round = r0 + (uint32_t)(lane % R);
+                const uint32_t q = round * waves + ((round & 1u) ? waves - 1u - me : me);
+                if (lane < 2 * R && round < rounds && q < n) {
+                    const int32_t i = scr.order[q];
+                    my_ptr = (int64_t)i * per_row + lane / R;
+                    my_row = scr.rows[i];
+                }
+            }
+            Vec<VEC> acc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r].zero();
+            // The pieces (window, row slot) come in a fixed order, and the first 64 entries of a piece are
+            // requested while the piece before it is multiplied out (as are the next 64 of a longer piece).
+            int32_t next_bound = my_ptr >= 0 && (int)xcd < windows ? scr.ptr[my_ptr + xcd] : 0;
+            EntryChunk cur = load_chunk(colidx, vals, __builtin_amdgcn_readlane(next_bound, 0),
+                                        __builtin_amdgcn_readlane(next_bound, R), lane);
+            for (int w = (int)xcd; w < windows; w += xcds) {
+                const int32_t bound = next_bound;
+                next_bound = my_ptr >= 0 && w + xcds < windows ? scr.ptr[my_ptr + w + xcds] : 0;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int32_t p0 = __builtin_amdgcn_readlane(bound, r);
+                    const int32_t p1 = __builtin_amdgcn_readlane(bound, R + r);
+                    // the piece after this one
+                    const int32_t np0 = r + 1 < R ? __builtin_amdgcn_readlane(bound, (r + 1) % R)
+                                                  : __builtin_amdgcn_readlane(next_bound, 0);
+                    const int32_t np1 = r + 1 < R ? __builtin_amdgcn_readlane(bound, R + (r + 1) % R)
+                                                  : __builtin_amdgcn_readlane(next_bound, R);
+                    if (p0 >= p1) {
+                        // nothing here (and nothing was requested for it)
+                        cur = load_chunk(colidx, vals, np0, np1, lane);
+                        continue;
+                    }
+                    for (int32_t base = p0; base < p1; base += kWave) {
+                        const int32_t after = base + kWave;
+                        const EntryChunk ahead = after < p1 ? load_chunk(colidx, vals, after, p1, lane)
+                                                            : load_chunk(colidx, vals, np0, np1, lane);
+                        const int cnt = p1 - base < kWave ? p1 - base : kWave;
+                        chunk_accumulate<VEC, OFF32, kOwnerDepth>(rows, acc[r], cur, 0, cnt);
+                        cur = ahead;
+                    }
+                }
+                __syncthreads();  // the compute unit's wavefronts take the next window together
+            }
+            // (the lane number through an opaque copy: the index arithmetic of the flush would otherwise be
+            // hoisted in front of the walk and hold some thirty registers throughout it)
+            int flush_lane = lane;
+            asm volatile("" : "+v"(flush_lane));
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int32_t row = __builtin_amdgcn_readlane(my_row, r);
+                if (row >= 0) panel_flush<1, kWave, VEC>(a, acc[r], row, k0, flush_lane);
+            }
         }
     }
 }
@@ -272,8 +420,8 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
 namespace {
 
 template <int G, int LC, int VEC>
-void launch_long_rows(const SpmmArgs& a, PanelScratch* scr, int windows, int xcds, int compute_units,
-                      hipStream_t s)
+void launch_long_rows(const SpmmArgs& a, const PanelView& scr, int windows, int xcds, int compute_units,
+                      uint32_t below, hipStream_t s)
 {
     const bool off32 = offsets_fit_32(a);
     // workgroups of each instance that one compute unit holds at once: the grid must be resident as a whole
@@ -289,10 +437,31 @@ void launch_long_rows(const SpmmArgs& a, PanelScratch* scr, int windows, int xcd
     if (grid < xcds) grid = xcds;
     if (off32)
         hipLaunchKernelGGL((panel_long_rows_kernel<G, LC, VEC, true>), dim3(grid), dim3(kBlock), 0, s, a, scr, windows,
-                           xcds);
+                           xcds, below);
     else
         hipLaunchKernelGGL((panel_long_rows_kernel<G, LC, VEC, false>), dim3(grid), dim3(kBlock), 0, s, a, scr, windows,
-                           xcds);
+                           xcds, below);
+}
+
+// The owner kernel for lists of at least *min_rows rows (half the wavefronts of a die: with fewer rows than that
+// most wavefronts would own nothing); returns that threshold so that the claiming kernel can stand back.
+template <int VEC>
+uint32_t launch_owner_rows(const SpmmArgs& a, const PanelView& scr, int windows, int xcds, int compute_units,
+                           hipStream_t s)
+{
+    const bool off32 = offsets_fit_32(a);
+    // one workgroup per compute unit (nothing depends on their all being resident: there is no waiting between them)
+    int grid = compute_units;
+    grid -= grid % xcds;
+    if (grid < xcds) grid = xcds;
+    const uint32_t min_rows = (uint32_t)(grid / xcds) * kOwnerWaves / 2;
+    if (off32)
+        hipLaunchKernelGGL((panel_owner_kernel<VEC, true>), dim3(grid), dim3(kOwnerBlock), 0, s, a.colidx, a.vals, a.B,
+                           a.C, scr, a.K, a.N, windows, xcds, min_rows);
+    else
+        hipLaunchKernelGGL((panel_owner_kernel<VEC, false>), dim3(grid), dim3(kOwnerBlock), 0, s, a.colidx, a.vals, a.B,
+                           a.C, scr, a.K, a.N, windows, xcds, min_rows);
+    return min_rows;
 }
 
 // Column windows of about window_bytes of B each, at most kPanelMaxWindows.
@@ -313,61 +482,90 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
 
 // The preparation both operators share: list of the rows of at least min_len
 // entries, their window pointers, and (zero_rows) zeros in their rows of C.
-// tile_cols = columns of B one item reads per row (a window holds window_bytes of such pieces).
-hipError_t launch_panel_preparation(const SpmmArgs& a, int64_t tile_cols, int32_t min_len, int64_t window_bytes,
-                                    bool zero_rows, int compute_units, hipStream_t s, PanelScratch** scratch,
-                                    int* windows)
+void launch_panel_preparation(const SpmmArgs& a, const PanelView& scr, int windows, int32_t window_rows,
+                              int32_t min_len, bool zero_rows, bool rank_rows, int compute_units, hipStream_t s)
 {
-    PanelScratch* scr = panel_scratch();
-    if (!scr) return hipErrorInvalidValue;
-    int32_t window_rows = 1;
-    plan_panels(a.K, tile_cols, window_bytes, windows, &window_rows);
     hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
     hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
                        min_len);
-    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, *windows,
+    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, windows,
                        window_rows, zero_rows ? 1 : 0);
-    *scratch = scr;
-    return hipGetLastError();
+    if (rank_rows) {
+        const uint32_t rows = scr.cap < (uint32_t)kRankMaxRows ? scr.cap : (uint32_t)kRankMaxRows;
+        hipLaunchKernelGGL(panel_rank_kernel, dim3((rows + kBlock / kRankLanes - 1) / (kBlock / kRankLanes)), dim3(kBlock),
+                           0, s, a.rowptr, scr);
+    }
+}
+
+// Lane layout of the SpMM window kernels: chunk lanes for the columns of a tile (at most kPanelTileLanes * 4
+// columns), the rest of the 64 lanes split the entries; and the columns of B one item reads per row.
+void spmm_panel_layout(int64_t N, int* wave_lc, int64_t* window_cols)
+{
+    int lc = 1;
+    while (lc < kPanelTileLanes && (int64_t)lc * 4 < N) lc *= 2;
+    *wave_lc = lc;
+    *window_cols = (int64_t)lc * 4 < N ? (int64_t)lc * 4 : N;
 }
 
 }  // namespace
 
+int64_t spmm_panels_workspace_bytes(int64_t K, int64_t N, int64_t window_bytes, int64_t cap)
+{
+    int wave_lc = 1, windows = 1;
+    int64_t window_cols = 1;
+    int32_t window_rows = 1;
+    spmm_panel_layout(N > 0 ? N : 1, &wave_lc, &window_cols);
+    plan_panels(K, window_cols, window_bytes, &windows, &window_rows);
+    return panel_workspace_bytes(cap, windows);
+}
+
+int64_t sddmm_panels_workspace_bytes(int64_t K, int64_t J, int64_t window_bytes, int64_t cap)
+{
+    int windows = 1;
+    int32_t window_rows = 1;
+    plan_panels(K, J > 0 ? J : 1, window_bytes, &windows, &window_rows);
+    return panel_workspace_bytes(cap, windows);
+}
+
 // Long rows (at least min_len entries) window by window, all other rows by the
 // row-split kernel with g lanes per row.  Requires vec == 4 (N % 4 == 0, 16-byte
-// aligned B and C).  lc and the other row-split arguments as for launch_row_split.
+// aligned B and C) and a workspace of spmm_panels_workspace_bytes(K, N, window_bytes, cap)
+// bytes.  lc and the other row-split arguments as for launch_row_split.
 hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                                   int tile_cols, int xcds, int compute_units, bool persistent, int32_t min_len,
-                                   int64_t window_bytes, hipStream_t s)
+                                   int tile_cols, int xcds, int compute_units, bool persistent, int block,
+                                   int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap, hipStream_t s)
 {
-    if (vec != 4 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
-    // one wavefront per item: chunk lanes for the columns of a tile (at most kPanelTileLanes * 4), the rest
-    // of the 64 lanes split the entries
-    int wave_lc = 1;
-    while (wave_lc < kPanelTileLanes && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
-    const int64_t window_cols = (int64_t)wave_lc * 4 < a.N ? (int64_t)wave_lc * 4 : a.N;
-    if ((a.N + window_cols - 1) / window_cols * kPanelMaxWindows * kPanelMaxRows > 0xffffffffLL)
-        return hipErrorInvalidValue;
-    PanelScratch* scr = nullptr;
-    int windows = 1;
-    hipError_t err =
-        launch_panel_preparation(a, window_cols, min_len, window_bytes, true, compute_units, s, &scr, &windows);
-    if (err != hipSuccess) return err;
+    if (vec != 4 || min_len < 1 || xcds < 1 || !workspace || cap < 1) return hipErrorInvalidValue;
+    int wave_lc = 1, windows = 1;
+    int64_t window_cols = 1;
+    int32_t window_rows = 1;
+    spmm_panel_layout(a.N, &wave_lc, &window_cols);
+    plan_panels(a.K, window_cols, window_bytes, &windows, &window_rows);
+    // the claiming kernel numbers its items (column tile, window, long row) with 32 bits
+    if ((a.N + window_cols - 1) / window_cols * windows * cap > 0xffffffffLL)
+        return launch_row_split(a, g, lc, vec, rows_per_slot, interleave, tile_cols, xcds, compute_units, persistent,
+                                block, s);
+    const PanelView scr = panel_view(workspace, cap, windows);
+    // a wavefront per row with all 64 lanes on column chunks: worth it from 128 columns on
+    const bool owners = wave_lc == kPanelTileLanes && a.N >= 128;
+    launch_panel_preparation(a, scr, windows, window_rows, min_len, true, owners, compute_units, s);
+    uint32_t below = 0xffffffffu;
+    if (owners) below = launch_owner_rows<4>(a, scr, windows, xcds, compute_units, s);
     switch (wave_lc) {
-        case 1: launch_long_rows<64, 1, 4>(a, scr, windows, xcds, compute_units, s); break;
-        case 2: launch_long_rows<32, 2, 4>(a, scr, windows, xcds, compute_units, s); break;
-        case 4: launch_long_rows<16, 4, 4>(a, scr, windows, xcds, compute_units, s); break;
-        case 8: launch_long_rows<8, 8, 4>(a, scr, windows, xcds, compute_units, s); break;
-        case 16: launch_long_rows<4, 16, 4>(a, scr, windows, xcds, compute_units, s); break;
-        case 32: launch_long_rows<2, 32, 4>(a, scr, windows, xcds, compute_units, s); break;
-        default: launch_long_rows<1, 64, 4>(a, scr, windows, xcds, compute_units, s); break;
+        case 1: launch_long_rows<64, 1, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        case 2: launch_long_rows<32, 2, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        case 4: launch_long_rows<16, 4, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        case 8: launch_long_rows<8, 8, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        case 16: launch_long_rows<4, 16, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        case 32: launch_long_rows<2, 32, 4>(a, scr, windows, xcds, compute_units, below, s); break;
+        default: launch_long_rows<1, 64, 4>(a, scr, windows, xcds, compute_units, below, s); break;
     }
-    err = hipGetLastError();
+    hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
 
     row_split_detail::Launch<false, true> f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units,
-                                            offsets_fit_32(a), persistent, 0, s,
-                                            RowSkip{&scr->count, (uint32_t)kPanelMaxRows, min_len}};
+                                            offsets_fit_32(a), persistent, 0, block, s,
+                                            RowSkip{&scr.head->count, scr.cap, min_len}};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -468,12 +666,12 @@ __device__ __forceinline__ void panel_sddmm_item(const SpmmArgs& a, const float*
 
 template <int G, int LC>
 __global__ __launch_bounds__(kBlock) void panel_sddmm_kernel(SpmmArgs a, const float* __restrict__ X1,
-                                                             float* __restrict__ out, PanelScratch* scr, int windows,
+                                                             float* __restrict__ out, PanelView scr, int windows,
                                                              int xcds)
 {
     __shared__ uint32_t s_claim;
-    const uint32_t n = scr->count;
-    if (n == 0 || n > (uint32_t)kPanelMaxRows) return;
+    const uint32_t n = scr.head->count;
+    if (n == 0 || n > scr.cap) return;
     const int lane = threadIdx.x % kWave;
     const int wave = threadIdx.x / kWave;
     const int per_row = windows + 1;
@@ -482,7 +680,7 @@ __global__ __launch_bounds__(kBlock) void panel_sddmm_kernel(SpmmArgs a, const f
     const uint32_t items = (uint32_t)(my_windows * n);
     for (;;) {  // claims as in panel_long_rows_kernel
         __syncthreads();
-        if (threadIdx.x == 0) s_claim = atomicAdd(&scr->next[xcd], (uint32_t)kPanelClaim);
+        if (threadIdx.x == 0) s_claim = atomicAdd(&scr.head->next[xcd], (uint32_t)kPanelClaim);
         __syncthreads();
         const uint32_t claim = s_claim;
         if (claim >= items) break;
@@ -491,9 +689,9 @@ __global__ __launch_bounds__(kBlock) void panel_sddmm_kernel(SpmmArgs a, const f
             if (it >= items) break;
             const int w = xcd + xcds * (int)(it / n);
             const int i = (int)(it % n);
-            const int32_t p0 = scr->ptr[(int64_t)i * per_row + w];
-            const int32_t p1 = scr->ptr[(int64_t)i * per_row + w + 1];
-            if (p0 < p1) panel_sddmm_item<G, LC>(a, X1, out, p0, p1, scr->rows[i], lane);
+            const int32_t p0 = scr.ptr[(int64_t)i * per_row + w];
+            const int32_t p1 = scr.ptr[(int64_t)i * per_row + w + 1];
+            if (p0 < p1) panel_sddmm_item<G, LC>(a, X1, out, p0, p1, scr.rows[i], lane);
         }
     }
 }
@@ -501,7 +699,7 @@ __global__ __launch_bounds__(kBlock) void panel_sddmm_kernel(SpmmArgs a, const f
 namespace {
 
 template <int G, int LC>
-void launch_sddmm_long_rows(const SpmmArgs& a, const float* X1, float* out, PanelScratch* scr, int windows, int xcds,
+void launch_sddmm_long_rows(const SpmmArgs& a, const float* X1, float* out, const PanelView& scr, int windows, int xcds,
                             int compute_units, hipStream_t s)
 {
     static const int per_cu = [] {
@@ -519,16 +717,20 @@ void launch_sddmm_long_rows(const SpmmArgs& a, const float* X1, float* out, Pane
 }  // namespace
 
 // a: M, K, N = J, rowptr, colidx, vals, B = X2T.  Requires 16-byte loads (J % 4 == 0,
-// aligned X1 and X2T) and 32 <= J <= 256.
+// aligned X1 and X2T), 32 <= J <= 256 and a workspace of
+// sddmm_panels_workspace_bytes(K, J, window_bytes, cap) bytes.
 hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, int g, int per_lane, int xcds,
                                int compute_units, int64_t nnz_hint, int32_t min_len, int64_t window_bytes,
-                               hipStream_t s)
+                               void* workspace, int64_t cap, hipStream_t s)
 {
-    if (a.N % 4 != 0 || a.N < 32 || a.N > 256 || min_len < 1 || xcds < 1) return hipErrorInvalidValue;
-    PanelScratch* scr = nullptr;
+    if (a.N % 4 != 0 || a.N < 32 || a.N > 256 || min_len < 1 || xcds < 1 || !workspace || cap < 1)
+        return hipErrorInvalidValue;
     int windows = 1;
-    hipError_t err = launch_panel_preparation(a, a.N, min_len, window_bytes, false, compute_units, s, &scr, &windows);
-    if (err != hipSuccess) return err;
+    int32_t window_rows = 1;
+    plan_panels(a.K, a.N, window_bytes, &windows, &window_rows);
+    if ((int64_t)windows * cap > 0xffffffffLL) return hipErrorInvalidValue;
+    const PanelView scr = panel_view(workspace, cap, windows);
+    launch_panel_preparation(a, scr, windows, window_rows, min_len, false, false, compute_units, s);
     int wave_lc = 8;
     while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
     switch (wave_lc) {
@@ -537,10 +739,10 @@ hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, i
         case 32: launch_sddmm_long_rows<2, 32>(a, X1, out, scr, windows, xcds, compute_units, s); break;
         default: launch_sddmm_long_rows<1, 64>(a, X1, out, scr, windows, xcds, compute_units, s); break;
     }
-    err = hipGetLastError();
+    const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     return launch_sddmm_skip(a, X1, out, g, per_lane, compute_units, nnz_hint,
-                             RowSkip{&scr->count, (uint32_t)kPanelMaxRows, min_len}, s);
+                             RowSkip{&scr.head->count, scr.cap, min_len}, s);
 }
 
 }  // namespace sgap

@@ -28,10 +28,10 @@
 namespace sgap {
 
 hipError_t launch_row_split(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
-                            int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s)
+                            int tile_cols, int xcds, int compute_units, bool persistent, int block, hipStream_t s)
 {
     row_split_detail::Launch<false> f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units,
-                                      offsets_fit_32(a), persistent, 0, s};
+                                      offsets_fit_32(a), persistent, 0, block, s};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }

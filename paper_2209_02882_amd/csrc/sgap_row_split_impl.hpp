@@ -10,19 +10,23 @@ namespace sgap {
 
 constexpr int kStageCap = 2048;  // (column, value) pairs per LDS chunk: 16 KB
 constexpr int kRowCap = 1024;    // rowptr entries kept in LDS per row block (+1)
+constexpr int kRowSplitMaxBlock = 512;  // threads per workgroup: 128, 256 or 512, chosen at launch
 
 // PARTIAL: the G members of a row reduce in sub-groups of `reduce_members`
 // (a power of two below G) and the first member of every sub-group adds its
 // sum to C with atomics; C must hold zeros before the launch.
 // SKIP: leave the rows described by `skip` alone.
+// The workgroup size (the paper's blockSz, Section 7.2) is the launch's: SLOTS = blockDim.x / (G*LC)
+// groups work side by side on the rows of a row block.
 template <int G, int LC, int VEC, bool OFF32, bool PARTIAL, bool SKIP = false>
-__global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot,
-                                                           int interleave, int reduce_members, RowSkip skip)
+__global__ __launch_bounds__(kRowSplitMaxBlock) void row_split_kernel(SpmmArgs a, TileSched ts, int rows_per_slot,
+                                                                      int interleave, int reduce_members, RowSkip skip)
 {
     __shared__ StagedEntry s_A[kStageCap];
     __shared__ int32_t s_rp[kRowCap + 1];
     constexpr int SPAN = G * LC;
-    constexpr int SLOTS = kBlock / SPAN;
+    const int block = blockDim.x;
+    const int SLOTS = block / SPAN;
 
     const int slot = threadIdx.x / SPAN;
     const int member = (threadIdx.x / LC) % G;
@@ -56,7 +60,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
 
         __syncthreads();  // everyone is done with the previous item's LDS contents
         if (rp_in_lds) {
-            for (int i = threadIdx.x; i <= block_rows; i += kBlock)
+            for (int i = threadIdx.x; i <= block_rows; i += block)
                 s_rp[i] = a.rowptr[row_first + i];
             __syncthreads();
         }
@@ -77,7 +81,7 @@ __global__ __launch_bounds__(kBlock) void row_split_kernel(SpmmArgs a, TileSched
             for (uint32_t base = nz_first;; base += kStageCap) {  // runs at least once: empty rows get stored
                 const uint32_t cnt = nz_last - base < (uint32_t)kStageCap ? nz_last - base : (uint32_t)kStageCap;
                 if (base != nz_first || k0 != (int64_t)col_tile * ts.tile_cols) __syncthreads();
-                stage_entries(a, base, cnt, s_A);
+                stage_entries(a, base, cnt, s_A, block);
                 __syncthreads();
                 // rows of this slot that have entries in the chunk (or are empty)
                 while (row < my_last) {
@@ -150,26 +154,28 @@ struct Launch {
     int rows_per_slot, interleave, tile_cols, xcds, compute_units;
     bool off32, persistent;
     int reduce_members;
+    int block;  // threads per workgroup: 128, 256 or 512 (at least G*LC)
     hipStream_t s;
     RowSkip skip = {nullptr, 0, 0};
 
     // workgroups of this instance that one compute unit can hold at once
     template <typename K>
-    static int resident_per_cu(K kernel)
+    static int resident_per_cu(K kernel, int block)
     {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n < 1) n = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, block, 0) != hipSuccess || n < 1) n = 1;
         return n;
     }
 
     template <int G, int LC, int VEC>
     void operator()() const
     {
-        // a persistent grid must be resident all at once
-        static const int per_cu_32 = resident_per_cu(row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>);
-        static const int per_cu_64 = resident_per_cu(row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>);
-        const int max_grid = persistent ? compute_units * (off32 ? per_cu_32 : per_cu_64) : 0x7fffffff;
-        constexpr int slots = kBlock / (G * LC);
+        // a persistent grid must be resident all at once (asked of the runtime only for such launches)
+        int max_grid = 0x7fffffff;
+        if (persistent)
+            max_grid = compute_units * (off32 ? resident_per_cu(row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>, block)
+                                              : resident_per_cu(row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>, block));
+        const int slots = block / (G * LC);
         const int64_t rows_per_block = (int64_t)slots * rows_per_slot;
         TileSched ts;
         ts.row_blocks = (a.M + rows_per_block - 1) / rows_per_block;
@@ -183,10 +189,10 @@ struct Launch {
         if (wgs_per_xcd > ts.items_per_xcd) wgs_per_xcd = ts.items_per_xcd;
         const unsigned grid = (unsigned)(wgs_per_xcd * xcds);
         if (off32)
-            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>), dim3(grid), dim3(kBlock), 0, s, a,
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, true, PARTIAL, SKIP>), dim3(grid), dim3(block), 0, s, a,
                                ts, rows_per_slot, interleave, reduce_members, skip);
         else
-            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>), dim3(grid), dim3(kBlock), 0, s, a,
+            hipLaunchKernelGGL((row_split_kernel<G, LC, VEC, false, PARTIAL, SKIP>), dim3(grid), dim3(block), 0, s, a,
                                ts, rows_per_slot, interleave, reduce_members, skip);
     }
 };

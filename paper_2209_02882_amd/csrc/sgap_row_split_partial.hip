@@ -7,11 +7,12 @@
 namespace sgap {
 
 hipError_t launch_row_split_partial(const SpmmArgs& a, int g, int r, int lc, int vec, int rows_per_slot,
-                                    int tile_cols, int xcds, int compute_units, bool persistent, hipStream_t s)
+                                    int tile_cols, int xcds, int compute_units, bool persistent, int block,
+                                    hipStream_t s)
 {
     if (r < 1 || r >= g || (r & (r - 1)) != 0) return hipErrorInvalidValue;
     row_split_detail::Launch<true> f{a, rows_per_slot, 1, tile_cols, xcds, compute_units,
-                                     offsets_fit_32(a), persistent, r, s};
+                                     offsets_fit_32(a), persistent, r, block, s};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }

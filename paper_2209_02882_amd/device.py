@@ -36,6 +36,29 @@ class DeviceProblem:
                                  group, binding.STRATEGIES[strategy], binding.SCHEDULES[schedule],
                                  nnz_hint=nnz_hint, stream=stream)
 
+    def workspace_for(self, config):
+        """Device workspace (uint8 tensor) of the size the configuration needs, or None."""
+        p = self.p
+        size = binding.sgap_spmm_csr_workspace_size(p.M, p.K, p.N, config)
+        return torch.empty(size, dtype=torch.uint8, device=self.rowptr.device) if size else None
+
+    def launch_cfg(self, C, config, workspace=None, nnz_hint=None, stream=None):
+        """Enqueue C = A*B for one configuration (asynchronous)."""
+        p = self.p
+        binding.sgap_spmm_csr_cfg(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, self.B, C, config,
+                                  nnz_hint=nnz_hint, workspace=workspace, stream=stream)
+
+    def run_cfg(self, config, workspace=None, poison=True, C=None):
+        if C is None:
+            C = self.new_output()
+        if poison:
+            C.fill_(float("nan"))
+        if workspace is None:
+            workspace = self.workspace_for(config)
+        self.launch_cfg(C, config, workspace)
+        torch.cuda.synchronize()
+        return C
+
     def launch_gr(self, C, group, reduce_size, nnz_hint=None, stream=None):
         """Enqueue the row-split point with `group` lanes per row reducing in
         sub-groups of `reduce_size` lanes (asynchronous)."""
@@ -55,6 +78,19 @@ class DeviceProblem:
         p = self.p
         binding.sgap_sddmm_csr(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, X1, self.B, out,
                                group, binding.STRATEGIES[strategy], nnz_hint=nnz_hint, stream=stream)
+
+    def run_sddmm_windows(self, X1, group, strategy, long_row_min, window_kb=0, max_long_rows=0, poison=True):
+        p = self.p
+        out = torch.empty(p.nnz, dtype=torch.float32, device=self.rowptr.device)
+        if poison:
+            out.fill_(float("nan"))
+        size = binding.sgap_sddmm_csr_workspace_size(p.K, p.N, window_kb, max_long_rows)
+        ws = torch.empty(size, dtype=torch.uint8, device=self.rowptr.device) if size else None
+        binding.sgap_sddmm_csr_windows(p.M, p.K, p.N, self.rowptr, self.colidx, self.vals, X1, self.B, out, group,
+                                       binding.STRATEGIES[strategy], long_row_min, window_kb, max_long_rows,
+                                       workspace=ws)
+        torch.cuda.synchronize()
+        return out
 
     def run_sddmm(self, X1, group, strategy, poison=True):
         out = torch.empty(self.p.nnz, dtype=torch.float32, device=self.rowptr.device)

@@ -11,10 +11,13 @@ from paper_2209_02882_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "sgap.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sgap_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(headers=("sgap.h", "sgap_debug.h")):
+    names = set()
+    for header in headers:
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(sgap_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported_and_bound():
@@ -22,9 +25,73 @@ def test_header_symbols_are_exported_and_bound():
     names = declared_symbols()
     assert "sgap_spmm_csr" in names and "sgap_spmm_csr_ex" in names
     for name in names:
-        assert hasattr(lib, name), f"{name} declared in sgap.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in a header but not exported"
         assert name in binding.EXPORTS, f"{name} has no Python binding signature"
     assert sorted(binding.EXPORTS) == names
+
+
+def test_application_header_holds_no_test_scaffolding():
+    public = declared_symbols(("sgap.h",))
+    assert not [n for n in public if n.startswith(("sgap_debug_", "sgap_profile_"))] and "sgap_copy_f32" not in public
+    for name in ("sgap_spmm_csr_cfg", "sgap_spmm_csr_workspace_size", "sgap_autotune_csr_cfg", "sgap_sddmm_csr_windows"):
+        assert name in public
+
+
+def test_configuration_defaults_workspace_size_and_checks():
+    lib = binding.load()
+    c = binding.make_config(8, "parallel", "row_split")
+    assert c.as_dict() == dict(schedule=0, strategy=0, group_size=8, reduce_size=0, block_size=0, tile_cols=0,
+                               rows_per_group=0, xcd_remap=-1, persistent=0, nnz_tile=0, wave_rows=0, long_row_min=0,
+                               window_kb=0, max_long_rows=0)
+    assert lib.sgap_config_init(None) == binding.SGAP_ERR_INVALID_ARG
+    size = binding.sgap_spmm_csr_workspace_size
+    assert size(1000, 1000, 64, c) == 0  # long rows are not set apart
+    c.long_row_min = 512
+    # automatic window: 3072 KiB of B = 12288 rows of 64 columns -> 1 window over K = 1000; default list of 8192 rows
+    assert size(1000, 1000, 64, c) == 256 + 4 * 8192 * (1 + 3)
+    c.window_kb, c.max_long_rows = 16, 100
+    assert size(1000, 1000, 64, c) == 256 + (4 * 100 * (16 + 3) + 255) // 256 * 256  # 64 rows per window -> 16 windows
+    assert size(1000, 1000, 62, c) == 0  # needs 16-byte loads
+    c.schedule = binding.SGAP_SCHED_NNZ_BALANCED
+    assert size(1000, 1000, 64, c) == 0
+    c.schedule = binding.SGAP_SCHED_ROW_SPLIT
+    ptrs = (0x1000, 0x2000, 0x3000, 0x4000, 0x5000)
+    # the path applies (fake pointers are 16-byte aligned) and no workspace comes with the call
+    assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(c), -1, None, 0, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"workspace" in lib.sgap_last_error()
+    assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(c), -1, 0x7000, 64, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(c), -1, 0x7010, 1 << 20, None) == binding.SGAP_ERR_INVALID_ARG
+    assert b"aligned" in lib.sgap_last_error()
+    assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, None, -1, None, 0, None) == binding.SGAP_ERR_INVALID_ARG
+    for field, bad in [("block_size", 64), ("block_size", 1024), ("tile_cols", -1), ("rows_per_group", -1),
+                       ("xcd_remap", 2), ("nnz_tile", 300), ("long_row_min", -1), ("window_kb", -1),
+                       ("max_long_rows", -1), ("max_long_rows", (1 << 20) + 1), ("reduce_size", 3),
+                       ("reduce_size", 16), ("group_size", 3), ("strategy", 2), ("schedule", 2), ("wave_rows", 2)]:
+        bad_c = binding.make_config(8, "parallel", "row_split")
+        setattr(bad_c, field, bad)
+        assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(bad_c), -1, None, 0, None) == \
+            binding.SGAP_ERR_INVALID_ARG, field
+        assert lib.sgap_spmm_csr_workspace_size(4, 4, 4, ctypes.byref(bad_c)) == -1, field
+    # reduce_size below group_size belongs to the row-split parallel point only
+    for st, sc in [("serial", "row_split"), ("parallel", "nnz_balanced")]:
+        bad_c = binding.make_config(8, st, sc, reduce_size=2)
+        assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(bad_c), -1, None, 0, None) == binding.SGAP_ERR_INVALID_ARG
+    # the SDDMM twin
+    sd = binding.sgap_sddmm_csr_workspace_size
+    assert sd(1000, 64) == 256 + 4 * 8192 * (1 + 3)  # 2048 KiB windows: 8192 rows of 64 columns
+    assert sd(1000, 16) == 0 and sd(1000, 260) == 0 and sd(1000, 66) == 0
+    assert lib.sgap_sddmm_csr_workspace_size(-1, 64, 0, 0) == -1
+    assert lib.sgap_sddmm_csr_windows(4, 4, 64, *ptrs, 0x6000, 8, 0, 10, 100, 0, 0, None, 0, None) == \
+        binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_sddmm_csr_windows(4, 4, 64, *ptrs, 0x6000, 8, 0, 10, -1, 0, 0, None, 0, None) == \
+        binding.SGAP_ERR_INVALID_ARG
+    # the wide tuner checks its arguments before anything else
+    best = binding.TunedPoint()
+    pbest = ctypes.cast(ctypes.pointer(best), ctypes.c_void_p)
+    assert lib.sgap_autotune_csr_cfg(4, 4, 4, *ptrs, -1, 1, None, 0, None, 0, None, None, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_autotune_csr_cfg(4, 4, 4, *ptrs, -1, 0, None, 0, None, 0, None, pbest, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_autotune_csr_cfg(4, 4, 4, *ptrs, -1, 1, None, 0, None, 5, None, pbest, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_autotune_csr_cfg(0, 4, 4, *ptrs, -1, 1, None, 0, None, 0, None, pbest, None) == binding.SGAP_ERR_INVALID_ARG
 
 
 def test_version_and_status_strings():
@@ -244,9 +311,14 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     src = tmp_path / "use_sgap.c"
     src.write_text(
         '#include "sgap.h"\n'
+        '#include "sgap_debug.h"\n'
         "int main(void)\n{\n"
         "    float c[4];\n"
+        "    sgap_config cfg;\n"
         "    int rc = sgap_spmm_csr(0, 0, 0, 0, 0, 0, 0, c, 8, SGAP_REDUCE_PARALLEL, 0);\n"
+        "    rc |= sgap_config_init(&cfg);\n"
+        "    rc |= sgap_spmm_csr_cfg(0, 0, 0, 0, 0, 0, 0, c, &cfg, -1, 0, 0, 0);\n"
+        "    rc |= sgap_profile_enable(0);\n"
         "    return rc == SGAP_OK && sgap_version() >= 100 ? 0 : 1;\n"
         "}\n")
     inc = os.path.join(root, "include")

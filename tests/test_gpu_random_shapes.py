@@ -32,11 +32,14 @@ def draw_case(seed):
     rowptr, colidx = wl.csr_from_lengths(rng, ln.astype(np.int64), K)
     vals = wl.fill_values(rng, colidx.size, True)
     B = wl.fill_values(rng, K * N, True).reshape(K, N)
+    # per-call knobs of sgap_spmm_csr_cfg (drawn in this order, so that a seed keeps its case)
     knobs = {
-        binding.SGAP_TUNE_NNZ_TILE: int(rng.choice([0, 0, 256, 512, 2048])),
-        binding.SGAP_TUNE_LONG_ROW_MIN: int(rng.choice([0, 0, 50, 1000])),
-        binding.SGAP_TUNE_PANEL_WINDOW_KB: int(rng.choice([0, 1, 16])),
+        "nnz_tile": int(rng.choice([0, 0, 256, 512, 2048])),
+        "long_row_min": int(rng.choice([0, 0, 50, 1000])),
+        "window_kb": int(rng.choice([0, 1, 16])),
     }
+    knobs["block_size"] = int(rng.choice([0, 128, 256, 512]))
+    knobs["max_long_rows"] = int(rng.choice([0, 3, 700]))
     X1 = wl.fill_values(rng, M * N, True).reshape(M, N)
     return wl.SpmmProblem(f"random {kind}", M, K, N, rowptr, colidx, vals, B), X1, knobs
 
@@ -47,23 +50,23 @@ def test_random_case(seed):
     print(f"seed {seed}: {p.name} M={p.M} K={p.K} N={p.N} nnz={p.nnz} knobs={knobs}", flush=True)
     C_ref, _ = oracle.spmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, nthreads=8, bound=False)
     dp = DeviceProblem(p)
-    try:
-        for knob, value in knobs.items():
-            binding.sgap_set_tuning(knob, value)
-        for pt in POINTS:
-            for hint in (None, -1):  # the host knows the number of stored entries, or does not
-                got = dp.run(*pt, nnz_hint=hint).cpu().numpy().astype(np.float64)
-                assert np.array_equal(got, C_ref), f"seed {seed} {pt} nnz_hint={hint}"
-        for g, r in GR_POINTS[::3]:
-            got = dp.run_gr(g, r).cpu().numpy().astype(np.float64)
-            assert np.array_equal(got, C_ref), f"seed {seed} g={g} r={r}"
-        if p.nnz:
-            ref, _ = oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=8, bound=False)
-            X1d = torch.from_numpy(X1).cuda()
-            for st in ("parallel", "serial"):
-                for g in binding.GROUP_SIZES:
-                    got = dp.run_sddmm(X1d, g, st).cpu().numpy().astype(np.float64)
-                    assert np.array_equal(got, ref), f"seed {seed} sddmm g={g} {st}"
-    finally:
-        for knob in knobs:
-            binding.sgap_set_tuning(knob, 0)
+    C = dp.new_output()
+    for pt in POINTS:
+        cfg = binding.make_config(*pt, **knobs)
+        ws = dp.workspace_for(cfg)
+        for hint in (None, -1):  # the host knows the number of stored entries, or does not
+            C.fill_(float("nan"))
+            dp.launch_cfg(C, cfg, ws, nnz_hint=hint)
+            got = C.cpu().numpy().astype(np.float64)
+            assert np.array_equal(got, C_ref), f"seed {seed} {pt} nnz_hint={hint}"
+    for g, r in GR_POINTS[::3]:
+        got = dp.run_cfg(binding.make_config(g, "parallel", "row_split", reduce_size=r, block_size=knobs["block_size"]))
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), C_ref), f"seed {seed} g={g} r={r}"
+    if p.nnz:
+        ref, _ = oracle.sddmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, X1, p.B, nthreads=8, bound=False)
+        X1d = torch.from_numpy(X1).cuda()
+        for st in ("parallel", "serial"):
+            for g in binding.GROUP_SIZES:
+                got = dp.run_sddmm_windows(X1d, g, st, knobs["long_row_min"], knobs["window_kb"],
+                                           knobs["max_long_rows"]).cpu().numpy().astype(np.float64)
+                assert np.array_equal(got, ref), f"seed {seed} sddmm g={g} {st}"
