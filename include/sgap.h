@@ -266,6 +266,36 @@ int sgap_spmm_csr_cfg(int64_t M, int64_t K, int64_t N,
                       void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * sgap_spmm_csr_cfg for callers that cannot allocate device memory, not even
+ * for a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The same call with the working memory of the window
+ * path in an array of 8 MiB (8,388,608 bytes) that the library holds on every
+ * GPU it runs on until the process ends; no workspace arguments, and neither
+ * this call nor anything it calls allocates or frees (no hipMalloc, no
+ * hipFree, no allocating library routine).  The caller still passes operands
+ * and result.
+ *   - A shape and configuration whose sgap_spmm_csr_workspace_size exceeds
+ *     8,388,608 bytes is refused with SGAP_ERR_UNSUPPORTED before anything is
+ *     launched (say, more windows or a longer list than fit: lower
+ *     max_long_rows or raise window_kb), with the two sizes in
+ *     sgap_last_error().  A configuration that needs no working memory runs as
+ *     sgap_spmm_csr_cfg does.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the last
+ *     call's contents; the call resets what it reads before writing.  Calls
+ *     that may overlap in time on one GPU (two streams, two threads) race on
+ *     it: the caller must order them.  sgap_spmm_csr_cfg with two workspaces
+ *     is the entry point for overlapping calls.
+ *   - The first call on a device looks up the array's device address
+ *     (hipGetSymbolAddress, with that device current); make it outside a
+ *     graph capture.
+ * Results, other arguments and errors as for sgap_spmm_csr_cfg.
+ */
+int sgap_spmm_csr_cfg_static(int64_t M, int64_t K, int64_t N,
+                             const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                             const float* B, float* C,
+                             const sgap_config* config, int64_t nnz_hint, void* stream);
+
+/*
  * Sampled dense-dense matrix product on the pattern of a CSR matrix, the
  * SDDMM form of the paper's Section 2.1 (third form under Eq. 1):
  *   out_vals[p] = vals[p] * sum_{j<J} X1[row(p), j] * X2T[colidx[p], j]

@@ -40,6 +40,7 @@ EXPORTS = {
     "sgap_config_init": (_int, [_p]),
     "sgap_spmm_csr_workspace_size": (_i64, [_i64, _i64, _i64, _p]),
     "sgap_spmm_csr_cfg": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p, _i64, _p]),
+    "sgap_spmm_csr_cfg_static": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _i64, _p]),
     "sgap_autotune_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _p, _p]),
     "sgap_autotune_csr_cfg": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _int, _p, _i64, _p, _int, _p, _p, _p]),
     "sgap_sddmm_csr": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _int, _int, _i64, _p]),
@@ -365,6 +366,14 @@ def sgap_autotune_csr(M, K, N, rowptr, colidx, vals, B, C, nnz_hint=None, reps=3
                                     ctypes.cast(table, ctypes.c_void_p), ctypes.cast(ctypes.pointer(best), ctypes.c_void_p),
                                     _stream_ptr(stream)))
     return best, list(table)
+
+
+def sgap_spmm_csr_cfg_static(M, K, N, rowptr, colidx, vals, B, C, config: Config, nnz_hint=None, stream=None) -> None:
+    """sgap_spmm_csr_cfg with the working memory in the library's built-in array (no allocation anywhere)."""
+    ptrs = _spmm_args(M, K, N, rowptr, colidx, vals, B, C)
+    if nnz_hint is None:
+        nnz_hint = colidx.numel()
+    _check(load().sgap_spmm_csr_cfg_static(M, K, N, *ptrs, ctypes.byref(config), int(nnz_hint), _stream_ptr(stream)))
 
 
 class TunedPoint(ctypes.Structure):

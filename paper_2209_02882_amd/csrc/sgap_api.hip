@@ -140,6 +140,10 @@ hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t 
 
 // ---------------------------------------------------------------------------
 
+// Working memory of sgap_spmm_csr_cfg_static: one copy per GPU, held until the process ends.
+constexpr int64_t kStaticScratchBytes = 8ll << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+
 namespace {
 
 int g_schedule = SGAP_SCHED_ROW_SPLIT;
@@ -544,6 +548,40 @@ int sgap_spmm_csr_cfg(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, co
 {
     if (!config) return fail(SGAP_ERR_INVALID_ARG, "config must not be null");
     return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, *config, nnz_hint, workspace, workspace_bytes, stream);
+}
+
+int sgap_spmm_csr_cfg_static(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                             const float* vals, const float* B, float* C, const sgap_config* config,
+                             int64_t nnz_hint, void* stream)
+{
+    if (!config) return fail(SGAP_ERR_INVALID_ARG, "config must not be null");
+    // what the call would ask of a caller's workspace must fit the built-in array
+    const int64_t need = sgap_spmm_csr_workspace_size(M, K, N, config);
+    if (need < 0) return SGAP_ERR_INVALID_ARG;
+    if (need > kStaticScratchBytes) {
+        char detail[160];
+        std::snprintf(detail, sizeof(detail),
+                      "this shape and configuration need %lld bytes of working memory; the built-in array holds %lld",
+                      (long long)need, (long long)kStaticScratchBytes);
+        return fail(SGAP_ERR_UNSUPPORTED, "%s", detail);
+    }
+    // this GPU's copy of the array: looked up once per device, with that device current
+    // (the array's name is a host-side stand-in, not a device address)
+    constexpr int kMaxDevices = 64;
+    static void* per_device[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(SGAP_ERR_HIP, "could not tell the current device");
+    if (!per_device[dev]) {
+        void* ptr = nullptr;
+        const hipError_t err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+        if (err != hipSuccess || !ptr)
+            return fail(SGAP_ERR_HIP, "could not locate the built-in working memory: %s", hipGetErrorString(err));
+        per_device[dev] = ptr;
+    }
+    // (nothing has to be cleared here: the first kernel of the window path resets the header of the
+    // workspace, the only part it reads before writing, on every call)
+    return spmm_impl(M, K, N, rowptr, colidx, vals, B, C, *config, nnz_hint, per_device[dev], kStaticScratchBytes, stream);
 }
 
 static int sddmm_impl(int64_t M, int64_t K, int64_t J, const int32_t* rowptr, const int32_t* colidx,
