@@ -1,17 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the CSR SpMM hot path on one MI355X.
 
-A "step" is one whole SpMM call (row-zeroing pass included where the point
-needs one) on a seeded synthetic workload that is resident in HBM.  All 28
-(group_size, strategy, schedule) points are swept briefly; the best one is
-then timed for exactly --steps steps and reported as ONE JSON line on stdout:
-effective GFLOP/s = 2*nnz*N/t, with the HBM roofline of the main kernel
-(minimal bytes nnz*8 + (M+1)*4 + K*N*4 + M*N*4 over its event-timed duration)
-and the CPU oracle timed on the host next to it.
+A "step" is one whole SpMM call (everything the call enqueues: row zeroing,
+the preparation of the window path, the kernels) on a seeded synthetic
+workload that is resident in HBM.  For each of the three large workloads
+(stencil27, rmat, skewed) every selectable path is swept briefly: the 28
+(group_size, strategy, schedule) points and the row-split points with their
+long rows taken by column windows; the best one is then timed for exactly
+--steps steps.  ONE JSON line goes to stdout: its top-level fields are the
+headline workload's (--workload, default skewed, the largest), `per_workload`
+carries all three, each with its HBM roofline (minimal bytes
+nnz*8 + (M+1)*4 + K*N*4 + M*N*4 over the event-timed duration of the whole
+call) and the CPU oracle timed on the host next to it.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -27,52 +33,66 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate
 # L1, measured with paper_2209_02882_amd/microbench/gather_bandwidth.hip
 # (profiles/microbenchmarks.md): 55-60 bytes per clock per compute unit.
 L1_GATHER_TBS = 36.0
-
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by the same counters on the library's plain copy kernel; keyed by
-# (workload, group, strategy, schedule).  See profiles/ for the runs.
-MEASURED_TRAFFIC_BYTES: dict = {
-    ("stencil27", 1, "parallel", "row_split"): 2_287_184_383,   # profiles/row_split_kernel_stencil27.md
-    ("stencil27", 1, "serial", "row_split"): 2_260_465_487,     # profiles/row_split_kernel_stencil27_serial.md
-    ("rmat", 16, "serial", "nnz_balanced"): 4_398_701_021,      # profiles/nnz_serial_kernel_rmat.md (main kernel)
-    ("skewed", 64, "serial", "nnz_balanced"): 59_904_989_739,   # profiles/nnz_serial_kernel_skewed.md (main kernel)
-    ("powerlaw", 16, "serial", "nnz_balanced"): 242_820_253,    # profiles/nnz_serial_kernel_powerlaw.md (main kernel)
-    # --long-row-min 1024: all five kernels of the call, profiles/panel_long_rows_kernel_skewed.md
-    ("skewed", 4, "serial", "row_split", 1024): 7_695_174_915,
-}
+LARGE_WORKLOADS = ("stencil27", "rmat", "skewed")
 
 
-# the same for --op sddmm, keyed by (workload, group, strategy)
-MEASURED_SDDMM_TRAFFIC_BYTES: dict = {
-    ("stencil27", 8, "parallel"): 4_622_814_612,   # profiles/sddmm_rowcache_kernel_stencil27.md
-    ("rmat", 8, "parallel"): 4_640_438_673,        # profiles/sddmm_rowcache_kernel_rmat.md
-    # --long-row-min 1024: all five kernels of the call, profiles/panel_sddmm_kernel_skewed.md
-    ("skewed", 16, "parallel", 1024): 8_349_418_150,
-}
+def kernel_source_hash() -> str:
+    """sha256 over the kernel sources (csrc/*.hip, *.hpp, sorted by name): what a
+    measured traffic figure is tied to."""
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2209_02882_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(src, name), "rb").read())
+    return h.hexdigest()
 
 
-# the same for --op mttkrp / ttm, keyed by (op, workload, point...)
-MEASURED_TENSOR_TRAFFIC_BYTES: dict = {
-    ("mttkrp", "tensor3", 8, "parallel"): 1_744_923_312,   # profiles/mttkrp_kernel_tensor3.md
-}
+def measured_traffic(op: str, workload: str, config: dict):
+    """HBM bytes per call from a committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE scaled by the same counters on a plain copy): the profiles/*.md that
+    holds a `traffic-record:` line for this operator, workload and configuration.
+    Returns (bytes, file) when the record was taken at the kernel sources as they
+    are now, else (None, reason): a figure from other sources says nothing about
+    these kernels."""
+    now = kernel_source_hash()
+    stale = None
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            if not line.startswith("traffic-record:"):
+                continue
+            rec = json.loads(line[len("traffic-record:"):])
+            if rec.get("op") != op or rec.get("workload") != workload or rec.get("config") != config:
+                continue
+            if rec.get("source_sha256") == now:
+                return int(rec["bytes"]), os.path.relpath(path, ROOT)
+            stale = os.path.relpath(path, ROOT)
+    return None, (f"{stale} was taken at other kernel sources" if stale else "no profile of this configuration")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_point(dp, torch, binding, C, point, iters):
-    g, st, sc = point
-    p = dp.p
-    args = (p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, g,
-            binding.STRATEGIES[st], binding.SCHEDULES[sc])
-    binding.sgap_spmm_csr_ex(*args)  # warm-up
+def time_config(dp, torch, C, cfg, ws, iters):
+    """Seconds per call of one configuration: a warm-up, then `iters` calls between synchronisations."""
+    dp.launch_cfg(C, cfg, ws)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(iters):
-        binding.sgap_spmm_csr_ex(*args)
+        dp.launch_cfg(C, cfg, ws)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / iters
+
+
+def describe(cfg, binding) -> dict:
+    """The fields of a configuration that name the path: the point, and every knob that is not left to the library."""
+    d = {"group_size": cfg.group_size, "strategy": binding.STRATEGY_NAMES[cfg.strategy],
+         "schedule": binding.SCHEDULE_NAMES[cfg.schedule]}
+    for k, v in cfg.as_dict().items():
+        if k not in ("group_size", "strategy", "schedule") and v != (-1 if k == "xcd_remap" else 0):
+            d[k] = v
+    return d
 
 
 def launch_stats(torch, launch, n, flush=None):
@@ -106,9 +126,10 @@ def ceilings(p):
     }
 
 
-def cpu_baseline(p):
+def cpu_baseline(p, seconds=10.0):
     """The oracle as it stands, timed on this host: all cores on the whole
-    workload (static row split), and one core on the first quarter of the rows."""
+    workload (static row split) repeated for about `seconds`, and one core on the
+    first quarter of the rows."""
     import oracle
 
     cores = len(os.sched_getaffinity(0))
@@ -117,7 +138,7 @@ def cpu_baseline(p):
         cores = min(cores, int(env))
     # all cores: the whole workload, repeated until about 10 s of wall time
     reps, t_all = 0, 0.0
-    while t_all < 10.0 and reps < 200:
+    while t_all < seconds and reps < 200:
         t0 = time.perf_counter()
         oracle.spmm_csr(p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.B, nthreads=cores)
         t_all += time.perf_counter() - t0
@@ -142,18 +163,23 @@ def cpu_baseline(p):
 
 
 def copy_reference(torch, binding):
-    """Streaming reference: the library's plain copy kernel over 1 GiB (also what
-    the hardware traffic counters are calibrated on).  Returns GB/s."""
-    n_copy = 256 * 1024 * 1024
-    src = torch.empty(n_copy, dtype=torch.float32, device="cuda:0").fill_(1.0)
+    """Streaming references over 1 GiB: the library's copy, read-only and write-only kernels (the copy is also
+    what the hardware traffic counters are calibrated on).  Returns GB/s of each, bytes moved over time."""
+    n = 256 * 1024 * 1024
+    src = torch.empty(n, dtype=torch.float32, device="cuda:0").fill_(1.0)
     dst = torch.empty_like(src)
-    binding.sgap_copy_f32(src, dst)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(10):
-        binding.sgap_copy_f32(src, dst)
-    torch.cuda.synchronize()
-    return 2.0 * n_copy * 4 * 10 / (time.perf_counter() - t0) / 1e9
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    out = {}
+    for name, mode, s_, d_, moved in (("copy", 0, src, dst, 2 * n * 4), ("read", 1, src, sink, n * 4),
+                                      ("write", 2, None, dst, n * 4)):
+        binding.sgap_stream_f32(s_, d_, n, mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            binding.sgap_stream_f32(s_, d_, n, mode)
+        torch.cuda.synchronize()
+        out[name] = moved * 10 / (time.perf_counter() - t0) / 1e9
+    return out
 
 
 def sddmm_cpu_baseline(p, X1):
@@ -197,16 +223,20 @@ def main_sddmm(a):
     X1h = wl.sddmm_left_operand(p)
     log(f"[bench] sddmm on {a.workload}: {p.row_stats()}")
     dp = DeviceProblem(p)
-    binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, a.long_row_min)
-    binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, a.window_kb)
     X1 = torch.from_numpy(X1h).cuda()
     out_vals = torch.empty(p.nnz, dtype=torch.float32, device="cuda:0")
     min_bytes = wl.sddmm_minimal_bytes(p)
     flops = 2 * p.nnz * p.N
+    ws_size = binding.sgap_sddmm_csr_workspace_size(p.K, p.N, a.window_kb) if a.long_row_min else 0
+    ws = torch.empty(ws_size, dtype=torch.uint8, device="cuda:0") if ws_size else None
 
     def run(g, st, n):
         for _ in range(n):
-            dp.launch_sddmm(X1, out_vals, g, st)
+            if a.long_row_min:
+                binding.sgap_sddmm_csr_windows(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, X1, dp.B, out_vals, g,
+                                               binding.STRATEGIES[st], a.long_row_min, a.window_kb, workspace=ws)
+            else:
+                dp.launch_sddmm(X1, out_vals, g, st)
 
     sweep = []
     if a.point:
@@ -242,6 +272,11 @@ def main_sddmm(a):
     kernel_avg_ms = kernel_ms / max(1, n_ev)
     achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
     copy_gbs = copy_reference(torch, binding)
+    key = {"group_size": g, "strategy": st}
+    if a.long_row_min:
+        key["long_row_min"] = a.long_row_min
+    traffic, traffic_from = (None, "J or the window was overridden") if a.ncols or a.window_kb else \
+        measured_traffic("sddmm", a.workload, key)
     out = {
         "metric": "SDDMM effective GFLOP/s (2*nnz*J/t), fp32, best (group_size, strategy) point",
         "value": flops / (ms_per_step * 1e-3) / 1e9,
@@ -257,16 +292,16 @@ def main_sddmm(a):
         "data": "synthetic",
         "config": {"workload": a.workload, "op": "sddmm", "M": p.M, "K": p.K, "J": p.N, "nnz": p.nnz,
                    "group_size": g, "strategy": st, "long_row_min": a.long_row_min},
-        "copy_kernel_gbs": copy_gbs,
+        "stream_kernels_gbs": copy_gbs,
         "roofline": {
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_SDDMM_TRAFFIC_BYTES.get((a.workload, g, st) + ((a.long_row_min,) if a.long_row_min else ()))
-            if a.ncols is None and not a.window_kb else None,
-            "kernel_avg_ms": kernel_avg_ms,
+            "traffic": traffic,
+            "traffic_from": traffic_from,
+            "call_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },
     }
@@ -346,6 +381,10 @@ def main_tensor(a):
     kernel_avg_ms = kernel_ms / max(1, n_ev)
     achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
     copy_gbs = copy_reference(torch, binding)
+    key = {"group_size": best[0], "strategy": best[1]}
+    if ttm:
+        key["schedule"] = best[2]
+    traffic, traffic_from = (None, "J was overridden") if a.ncols else measured_traffic(a.op, name, key)
     config = {"workload": name, "op": a.op, "I": p.I, "K": p.K, "L": p.L, "J": p.J, "fibers": p.fibers,
               "nnz": p.nnz, "group_size": best[0], "strategy": best[1]}
     if ttm:
@@ -365,15 +404,16 @@ def main_tensor(a):
         "dtype": "f32",
         "data": "synthetic",
         "config": config,
-        "copy_kernel_gbs": copy_gbs,
+        "stream_kernels_gbs": copy_gbs,
         "roofline": {
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TENSOR_TRAFFIC_BYTES.get((a.op, name, *best)) if a.ncols is None else None,
-            "kernel_avg_ms": kernel_avg_ms,
+            "traffic": traffic,
+            "traffic_from": traffic_from,
+            "call_avg_ms": kernel_avg_ms,
             "algorithmic_bytes": min_bytes,
         },
     }
@@ -409,6 +449,118 @@ def main_tensor(a):
     print(json.dumps(out), flush=True)
 
 
+def candidates(p, binding, with_gr):
+    """Every selectable path: the 28 points; the row-split points with their long rows by column windows
+    (where the operands allow 16-byte loads and the matrix has rows that long); optionally the 21 points
+    with the reduction narrower than the tiling."""
+    import numpy as np
+
+    from paper_2209_02882_amd.device import GR_POINTS, POINTS
+
+    out = [binding.make_config(*pt) for pt in POINTS]
+    longest = int(np.diff(p.rowptr.astype(np.int64)).max()) if p.M else 0
+    if p.N % 4 == 0:
+        for min_len in (1024, 4096):
+            if longest < min_len:
+                continue
+            for st, groups in (("serial", (1, 2, 4, 8)), ("parallel", (1, 4, 8))):
+                out += [binding.make_config(g, st, "row_split", long_row_min=min_len) for g in groups]
+    if with_gr:
+        out += [binding.make_config(g, "parallel", "row_split", reduce_size=r) for g, r in GR_POINTS]
+    return out
+
+
+def measure_spmm(a, name, torch, binding, wl, copy_gbs):
+    """Sweep, time and rate one workload; returns its record of the JSON line."""
+    from paper_2209_02882_amd.device import DeviceProblem
+
+    t0 = time.perf_counter()
+    p = wl.make_problem(name, N=a.ncols)
+    log(f"[bench] workload {name}: {p.row_stats()} generated in {time.perf_counter() - t0:.1f}s")
+    log(f"[bench] recipe: {wl.recipe(name)}; seed {wl.WORKLOADS[name][0]}")
+    dp = DeviceProblem(p)
+    C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
+    min_bytes = p.minimal_bytes()
+    flops = p.flops()
+
+    sweep = []
+    if a.point:
+        f = a.point.split(",")
+        knobs = dict(kv.split("=") for kv in f[3:])
+        best = binding.make_config(int(f[0]), f[1], f[2], **{k: int(v) for k, v in knobs.items()})
+    else:
+        best, best_t = None, None
+        for cfg in candidates(p, binding, a.gr):
+            ws = dp.workspace_for(cfg)
+            t = time_config(dp, torch, C, cfg, ws, a.sweep_iters)
+            d = describe(cfg, binding)
+            sweep.append({**d, "ms": t * 1e3, "gflops": flops / t / 1e9, "gbs": min_bytes / t / 1e9,
+                          "hbm_frac": min_bytes / t / 1e9 / HBM_PEAK_GBS})
+            log(f"[sweep] {name} {d} {t * 1e3:9.3f} ms {flops / t / 1e9:9.1f} GFLOP/s {min_bytes / t / 1e9:8.1f} GB/s")
+            if best_t is None or t < best_t:
+                best, best_t = cfg, t
+            del ws
+    ws = dp.workspace_for(best)
+    best_d = describe(best, binding)
+    log(f"[bench] {name}: timing {best_d}")
+
+    for _ in range(a.warmup):
+        dp.launch_cfg(C, best, ws)
+    binding.sgap_profile_enable(True)
+    binding.sgap_profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        dp.launch_cfg(C, best, ws)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    call_ms, n_ev = binding.sgap_profile_collect()
+    binding.sgap_profile_enable(False)
+    ms_per_step = elapsed / a.steps * 1e3
+    call_avg_ms = call_ms / max(1, n_ev)  # all kernels of a call, between events on the launch stream
+
+    # per-launch figures outside the timed region: median and minimum of 25
+    # launches, warm and with every cache overwritten before each launch
+    warm = launch_stats(torch, lambda: dp.launch_cfg(C, best, ws), 25)
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")  # 1 GiB
+    cold = launch_stats(torch, lambda: dp.launch_cfg(C, best, ws), 25, flush=flush)
+    del flush
+
+    achieved = min_bytes / (call_avg_ms * 1e-3) / 1e9
+    traffic, traffic_from = (None, "N or the point was overridden") if a.ncols else measured_traffic("spmm", name, best_d)
+    rec = {
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "ms_per_step": ms_per_step,
+        "config": {"workload": name, "M": p.M, "K": p.K, "N": p.N, "nnz": p.nnz, **best_d},
+        "hbm_gbs_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
+        "hbm_frac_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "launch_ms_warm": warm,
+        "launch_ms_caches_flushed": cold,
+        "ceilings": ceilings(p),
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "traffic_from": traffic_from,
+            "call_avg_ms": call_avg_ms,
+            "includes": "every kernel the call enqueues (row zeroing, window preparation)",
+            "algorithmic_bytes": min_bytes,
+        },
+    }
+    if not a.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(p, a.cpu_seconds)
+    if a.sweep_out and sweep:
+        with open(a.sweep_out.replace("{workload}", name), "w") as fh:
+            json.dump({"workload": name, "stats": p.row_stats(), "points": sweep}, fh, indent=1)
+    del dp, C, ws
+    torch.cuda.empty_cache()
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm", "mttkrp", "ttm"),
@@ -417,16 +569,23 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="stencil27")
+    ap.add_argument("--workload", default=None,
+                    help="the workload of the line's top-level fields (spmm: skewed, the largest configuration)")
+    ap.add_argument("--others", default=None,
+                    help="spmm: further workloads to carry in per_workload, comma separated (default: the other large "
+                         "configurations; '' for none)")
     ap.add_argument("--ncols", type=int, default=None, help="override N, the number of dense columns")
     ap.add_argument("--sweep-iters", type=int, default=3)
-    ap.add_argument("--point", default=None, help="fix the point: e.g. 8,parallel,row_split (skips the sweep)")
+    ap.add_argument("--point", default=None,
+                    help="fix the point: e.g. 8,parallel,row_split or 4,serial,row_split,long_row_min=1024 "
+                         "(skips the sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep-out", default=None, help="write the per-point sweep table (JSON) to this file")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="wall time of the oracle's all-core leg per workload")
+    ap.add_argument("--sweep-out", default=None,
+                    help="write the per-point sweep table (JSON) to this file ({workload} in the name is replaced)")
     ap.add_argument("--long-row-min", type=int, default=0,
-                    help="row-split schedule: rows of at least this many entries are produced by column windows "
-                         "(SGAP_TUNE_LONG_ROW_MIN; 0 = off)")
-    ap.add_argument("--window-kb", type=int, default=0, help="KiB of B per column window of that path (0 = 2048)")
+                    help="sddmm: entries of rows of at least this many entries are produced by column windows (0 = off)")
+    ap.add_argument("--window-kb", type=int, default=0, help="sddmm: KiB of X2T per column window of that path (0 = 2048)")
     ap.add_argument("--gr", action="store_true",
                     help="also sweep the row-split points with the reduction narrower than the tiling "
                          "(group_size lanes per row, sub-groups of reduce_size < group_size merged with atomics)")
@@ -436,8 +595,10 @@ def main():
                  "(the path would shard by row blocks of A and C with B replicated, no exchange step)")
 
     if a.op == "sddmm":
+        a.workload = a.workload or "stencil27"
         return main_sddmm(a)
     if a.op in ("mttkrp", "ttm"):
+        a.workload = a.workload or "tensor3"
         return main_tensor(a)
 
     import torch
@@ -448,117 +609,43 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     binding.load()
-
-    t0 = time.perf_counter()
-    p = wl.make_problem(a.workload, N=a.ncols)
-    log(f"[bench] workload {a.workload}: {p.row_stats()} generated in {time.perf_counter() - t0:.1f}s")
-    log(f"[bench] recipe: {wl.recipe(a.workload)}; seed {wl.WORKLOADS[a.workload][0]}")
-
-    from paper_2209_02882_amd.device import POINTS, DeviceProblem
-
-    dp = DeviceProblem(p)
-    C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
-    binding.sgap_set_tuning(binding.SGAP_TUNE_LONG_ROW_MIN, a.long_row_min)
-    binding.sgap_set_tuning(binding.SGAP_TUNE_PANEL_WINDOW_KB, a.window_kb)
-    min_bytes = p.minimal_bytes()
-    flops = p.flops()
-
-    sweep = []
-    if a.point:
-        g, st, sc = a.point.split(",")
-        best = (int(g), st, sc)
+    headline = a.workload or "skewed"
+    if a.others is None:
+        others = [w for w in LARGE_WORKLOADS if w != headline] if a.workload is None and not a.point else []
     else:
-        for pt in POINTS:
-            t = time_point(dp, torch, binding, C, pt, a.sweep_iters)
-            sweep.append({"group": pt[0], "strategy": pt[1], "schedule": pt[2], "ms": t * 1e3,
-                          "gflops": flops / t / 1e9, "gbs": min_bytes / t / 1e9,
-                          "hbm_frac": min_bytes / t / 1e9 / HBM_PEAK_GBS})
-            log(f"[sweep] g={pt[0]:2d} {pt[1]:8s} {pt[2]:12s} {t * 1e3:9.3f} ms "
-                f"{flops / t / 1e9:9.1f} GFLOP/s {min_bytes / t / 1e9:8.1f} GB/s")
-        b = min(sweep, key=lambda r: r["ms"])
-        best = (b["group"], b["strategy"], b["schedule"])
-    gr_sweep = []
-    if a.gr:
-        from paper_2209_02882_amd.device import GR_POINTS
-
-        for g_lanes, r_lanes in GR_POINTS:
-            dp.launch_gr(C, g_lanes, r_lanes)  # warm-up
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(a.sweep_iters):
-                dp.launch_gr(C, g_lanes, r_lanes)
-            torch.cuda.synchronize()
-            t = (time.perf_counter() - t0) / a.sweep_iters
-            gr_sweep.append({"group": g_lanes, "reduce": r_lanes, "ms": t * 1e3})
-            log(f"[sweep] row_split parallel g={g_lanes:2d} r={r_lanes:2d} {t * 1e3:9.3f} ms")
-    log(f"[bench] timing point {best}")
-
-    g, st, sc = best
-    args = (p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, g, binding.STRATEGIES[st], binding.SCHEDULES[sc])
-    for _ in range(a.warmup):
-        binding.sgap_spmm_csr_ex(*args)
-    binding.sgap_profile_enable(True)
-    binding.sgap_profile_collect()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        binding.sgap_spmm_csr_ex(*args)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernel_ms, n_ev = binding.sgap_profile_collect()
-    binding.sgap_profile_enable(False)
-    ms_per_step = elapsed / a.steps * 1e3
-    kernel_avg_ms = kernel_ms / max(1, n_ev)
-
+        others = [w for w in a.others.split(",") if w]
     copy_gbs = copy_reference(torch, binding)
 
-    # per-launch figures outside the timed region: median and minimum of 25
-    # launches, warm and with every cache overwritten before each launch
-    warm = launch_stats(torch, lambda: binding.sgap_spmm_csr_ex(*args), 25)
-    flush = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")  # 1 GiB
-    cold = launch_stats(torch, lambda: binding.sgap_spmm_csr_ex(*args), 25, flush=flush)
-    del flush
-
-    achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    per_workload = {}
+    for name in others + [headline]:
+        per_workload[name] = measure_spmm(a, name, torch, binding, wl, copy_gbs)
+    h = per_workload[headline]
     out = {
         "metric": "SpMM effective GFLOP/s (2*nnz*N/t), fp32, best (group_size, strategy, schedule) point",
-        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "value": h["value"],
         "unit": "GFLOP/s",
         "n_gpus": 1,
         "steps": a.steps,
         "warmup": a.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": h["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": a.workload, "M": p.M, "K": p.K, "N": p.N, "nnz": p.nnz,
-                   "group_size": g, "strategy": st, "schedule": sc, "long_row_min": a.long_row_min},
-        "hbm_gbs_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9,
-        "hbm_frac_minimal_bytes": min_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "copy_kernel_gbs": copy_gbs,
-        "launch_ms_warm": warm,
-        "launch_ms_caches_flushed": cold,
-        "ceilings": ceilings(p),
-        "roofline": {
-            "bound": "hbm",
-            "achieved": achieved,
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, g, st, sc) + ((a.long_row_min,) if a.long_row_min else ()))
-            if a.ncols is None and not a.window_kb else None,
-            "kernel_avg_ms": kernel_avg_ms,
-            "algorithmic_bytes": min_bytes,
-        },
+        "config": h["config"],
+        "hbm_gbs_minimal_bytes": h["hbm_gbs_minimal_bytes"],
+        "hbm_frac_minimal_bytes": h["hbm_frac_minimal_bytes"],
+        "stream_kernels_gbs": copy_gbs,
+        "launch_ms_warm": h["launch_ms_warm"],
+        "launch_ms_caches_flushed": h["launch_ms_caches_flushed"],
+        "ceilings": h["ceilings"],
+        "roofline": h["roofline"],
+        "kernel_source_sha256": kernel_source_hash(),
     }
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(p)
-    if a.sweep_out and sweep:
-        with open(a.sweep_out, "w") as f:
-            json.dump({"workload": a.workload, "stats": p.row_stats(), "points": sweep, "gr_points": gr_sweep}, f,
-                      indent=1)
+    if "cpu_baseline" in h:
+        out["cpu_baseline"] = h["cpu_baseline"]
+    out["per_workload"] = per_workload
     print(json.dumps(out), flush=True)
 
 

@@ -67,9 +67,17 @@ int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_ti
 int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
                                int compute_units, int forced_tile, int* tile, int* merge_on_chip);
 
-/* Plain device-to-device fp32 copy kernel (n elements, 16-byte aligned
- * buffers).  Used to calibrate hardware traffic counters and to report a
- * streaming-bandwidth reference. */
+/*
+ * Streaming kernels over n fp32 elements (16-byte aligned device buffers):
+ * what the memory system delivers to a kernel that does nothing but stream,
+ * reported next to the roofline fractions, and what the hardware traffic
+ * counters are calibrated on.
+ *   mode 0  copy src -> dst (sgap_copy_f32 is this)
+ *   mode 1  read src only; dst points to one float that is (in practice
+ *           never) written, so that the reads cannot be optimised away
+ *   mode 2  write dst only (the value 1.0f); src is ignored
+ */
+int sgap_stream_f32(const float* src, float* dst, int64_t n, int mode, void* stream);
 int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream);
 
 #ifdef __cplusplus

@@ -62,6 +62,7 @@ EXPORTS = {
     "sgap_debug_tile_deal": (_i64, [_i64, _int, _int, _p, _i64]),
     "sgap_debug_plan_nnz_serial": (_int, [_int, _int, _int, _i64, _int, _int, _p, _p]),
     "sgap_copy_f32": (_int, [_p, _p, _i64, _p]),
+    "sgap_stream_f32": (_int, [_p, _p, _i64, _int, _p]),
 }
 
 _lib = None
@@ -434,3 +435,11 @@ def sgap_copy_f32(src, dst, n=None, stream=None) -> None:
         raise ValueError("copy length exceeds a buffer")
     _check(load().sgap_copy_f32(_dev_ptr(src, torch.float32, "src"), _dev_ptr(dst, torch.float32, "dst"),
                                 int(n), _stream_ptr(stream)))
+
+
+def sgap_stream_f32(src, dst, n, mode, stream=None) -> None:
+    """mode 0: copy src -> dst; 1: read src only (dst: a one-float sink); 2: write dst only (see include/sgap_debug.h)."""
+    import torch
+
+    _check(load().sgap_stream_f32(_dev_ptr(src, torch.float32, "src") if src is not None else None,
+                                  _dev_ptr(dst, torch.float32, "dst"), int(n), int(mode), _stream_ptr(stream)))

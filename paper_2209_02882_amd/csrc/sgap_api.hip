@@ -34,14 +34,62 @@ __global__ void debug_group_seg_reduce_kernel(const float* __restrict__ in, cons
     out[lane] = group_seg_sum<G, LC>(in[lane], span[lane]);
 }
 
+// Streaming kernels: what the memory system delivers to a kernel that only streams (the context for the
+// roofline fractions, and what the hardware traffic counters are calibrated on).  Four 16-byte accesses in
+// flight per lane, non-temporal, a grid of a few workgroups per compute unit striding over the array.
+constexpr int kStreamUnroll = 4;
+
 __global__ __launch_bounds__(kBlock) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                           int64_t n)
 {
     const int64_t n4 = n / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
-        reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
-    for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const native_f4* __restrict__ s4 = reinterpret_cast<const native_f4*>(src);
+    native_f4* __restrict__ d4 = reinterpret_cast<native_f4*>(dst);
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + (kStreamUnroll - 1) * stride < n4; i += kStreamUnroll * stride) {
+        native_f4 t[kStreamUnroll];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) t[u] = __builtin_nontemporal_load(s4 + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) __builtin_nontemporal_store(t[u], d4 + i + u * stride);
+    }
+    for (; i < n4; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(s4 + i), d4 + i);
+    for (int64_t j = n4 * 4 + (int64_t)blockIdx.x * kBlock + threadIdx.x; j < n; j += stride) dst[j] = src[j];
+}
+
+// reads n floats; a lane whose sum is exactly `never` (no input makes it so in practice) writes it to sink, so
+// that the loads cannot be removed
+__global__ __launch_bounds__(kBlock) void read_f32_kernel(const float* __restrict__ src, int64_t n, float never,
+                                                          float* __restrict__ sink)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const native_f4* __restrict__ s4 = reinterpret_cast<const native_f4*>(src);
+    float sum = 0.0f;
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + (kStreamUnroll - 1) * stride < n4; i += kStreamUnroll * stride) {
+        native_f4 t[kStreamUnroll];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) t[u] = __builtin_nontemporal_load(s4 + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) sum += (t[u].x + t[u].y) + (t[u].z + t[u].w);
+    }
+    for (; i < n4; i += stride) {
+        const native_f4 t = __builtin_nontemporal_load(s4 + i);
+        sum += (t.x + t.y) + (t.z + t.w);
+    }
+    if (sum == never) *sink = sum;
+}
+
+__global__ __launch_bounds__(kBlock) void write_f32_kernel(float* __restrict__ dst, int64_t n, float value)
+{
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    native_f4* __restrict__ d4 = reinterpret_cast<native_f4*>(dst);
+    const native_f4 v = {value, value, value, value};
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) __builtin_nontemporal_store(v, d4 + i);
+    for (int64_t j = n4 * 4 + (int64_t)blockIdx.x * kBlock + threadIdx.x; j < n; j += stride) dst[j] = value;
 }
 
 // ---- sgap_validate_csr ------------------------------------------------------
@@ -130,9 +178,13 @@ hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, f
     if (!dispatch_group(g, lc, 1, LaunchDebugSegReduce{in, span, out, s})) return hipErrorInvalidValue;
     return hipGetLastError();
 }
-hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s)
+// mode 0: copy src -> dst; 1: read src only (dst is a one-float sink); 2: write dst only
+hipError_t launch_stream_f32(const float* src, float* dst, int64_t n, int mode, int compute_units, hipStream_t s)
 {
-    hipLaunchKernelGGL(copy_f32_kernel, dim3(256 * 16), dim3(kBlock), 0, s, src, dst, n);
+    const dim3 grid((unsigned)(compute_units * 8)), block(kBlock);
+    if (mode == 0) hipLaunchKernelGGL(copy_f32_kernel, grid, block, 0, s, src, dst, n);
+    else if (mode == 1) hipLaunchKernelGGL(read_f32_kernel, grid, block, 0, s, src, n, -1.2345678e38f, dst);
+    else hipLaunchKernelGGL(write_f32_kernel, grid, block, 0, s, dst, n, 1.0f);
     return hipGetLastError();
 }
 
@@ -931,15 +983,18 @@ int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t
     return SGAP_OK;
 }
 
-int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream)
+int sgap_stream_f32(const float* src, float* dst, int64_t n, int mode, void* stream)
 {
-    if (n < 0 || (n > 0 && (!src || !dst))) return fail(SGAP_ERR_INVALID_ARG, "bad copy arguments");
+    if (mode < 0 || mode > 2) return fail(SGAP_ERR_INVALID_ARG, "mode must be 0 (copy), 1 (read) or 2 (write)");
+    if (n < 0 || (n > 0 && ((mode != 2 && !src) || !dst))) return fail(SGAP_ERR_INVALID_ARG, "bad stream arguments");
     if (n == 0) return SGAP_OK;
-    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)
-        return fail(SGAP_ERR_INVALID_ARG, "copy buffers must be 16-byte aligned");
-    hipError_t err = sgap::launch_copy_f32(src, dst, n, reinterpret_cast<hipStream_t>(stream));
+    if ((reinterpret_cast<uintptr_t>(mode != 2 ? src : nullptr) | reinterpret_cast<uintptr_t>(mode != 1 ? dst : nullptr)) & 15)
+        return fail(SGAP_ERR_INVALID_ARG, "stream buffers must be 16-byte aligned");
+    hipError_t err = sgap::launch_stream_f32(src, dst, n, mode, compute_units(), reinterpret_cast<hipStream_t>(stream));
     if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
     return SGAP_OK;
 }
+
+int sgap_copy_f32(const float* src, float* dst, int64_t n, void* stream) { return sgap_stream_f32(src, dst, n, 0, stream); }
 
 }  // extern "C"

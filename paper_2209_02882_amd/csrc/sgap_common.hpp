@@ -226,7 +226,6 @@ hipError_t launch_mttkrp(int64_t I, int64_t K, int64_t L, int64_t J, const int32
                          int xcds, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
-hipError_t launch_copy_f32(const float* src, float* dst, int64_t n, hipStream_t s);
 
 // Generic (g, lc, vec) -> template instance dispatch.  F is a functor with
 //   template <int G, int LC, int VEC> void operator()() const
