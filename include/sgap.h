@@ -197,7 +197,13 @@ int sgap_spmm_csr_gr(int64_t M, int64_t K, int64_t N,
  *   nnz_tile        stored entries per tile of the nnz-balanced serial strategy:
  *                   256, 512, 1024 or 2048 (the two small ones need N % 4 == 0
  *                   and 16-byte aligned B and C, else the automatic choice is kept).
- *   wave_rows       reserved, must be 0.
+ *   wave_rows       lane layout of the row-split serial strategy: 1 = one wavefront
+ *                   owns group_size consecutive rows (at most 63) and all its 64
+ *                   lanes hold column chunks of c = 4, 2 or 1 columns, so that a
+ *                   stored entry is the same for the whole wavefront ({<g row,
+ *                   c col>, 1} of Section 6.1 with the widest lane layout; from 48
+ *                   columns on); -1 = never; 0 = automatic: only for the rows that
+ *                   long_row_min leaves to the row-split kernel, from 192 columns on.
  *   long_row_min    row-split schedule, reduce_size = group_size, N % 4 == 0 and
  *                   16-byte aligned B and C only (ignored otherwise): rows of at
  *                   least this many stored entries (say 1024) are taken out of the
@@ -456,8 +462,9 @@ int sgap_autotune_csr(int64_t M, int64_t K, int64_t N,
  * strategies with the long rows by column windows (long_row_min 512 and
  * 2048); then, around the fastest configuration so far, one knob at a time:
  * block_size 128 and 512, tile_cols 32, 64, 256, rows_per_group 1 to 16
- * (row-split parallel), window_kb 2048 and 4096 (window path, where the
- * workspace covers it), or nnz_tile 512, 1024, 2048 (nnz-balanced serial).
+ * (row-split parallel), wave_rows on and off (row-split serial), window_kb
+ * 2048 and 4096 (window path, where the workspace covers it), or nnz_tile 512,
+ * 1024, 2048 (nnz-balanced serial).
  * Timing of one configuration as in sgap_autotune_csr.
  *   workspace, workspace_bytes  as for sgap_spmm_csr_cfg; NULL/0: the window
  *          path is not rated

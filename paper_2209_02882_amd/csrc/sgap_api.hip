@@ -386,6 +386,15 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
             if (rows_per_slot < 1) rows_per_slot = 1;
             if (rows_per_slot > 1024 / slots) rows_per_slot = 1024 / slots > 0 ? 1024 / slots : 1;
         }
+        // Serial strategy in the widest lane layout: one wavefront per group_size consecutive rows (at most 63),
+        // all 64 lanes on column chunks of 1, 2 or 4 columns (the widest that fills most of the lanes).  On request
+        // from 48 columns on; by itself only for the rows that the window path leaves, from 192 columns on:
+        // what is left there is short rows (skewed: 0.63 -> 0.37 ms for that part), while on rows of a few dozen
+        // entries the narrower layout, with more rows in flight per workgroup, is faster (stencil27 at N = 256:
+        // 1.27 against 1.52 ms) and 8-byte loads cost as much as 16-byte ones (N = 128: 0.62 against 0.94 ms).
+        const bool wave_wanted = c.wave_rows == 1 ? N >= 48 : c.wave_rows == 0 && windows && N >= 192;
+        const int wave_vec = wave_wanted && !par && reduce_size == 0 ? (N > 128 ? vec : N > 64 ? (vec < 2 ? vec : 2) : 1) : 0;
+        const int wave_rows_count = group_size > 63 ? 63 : group_size;
         if (reduce_size != 0) {
             // every row receives atomic adds
             err = launch_nnz_zero_rows(a, vec, -1, s);
@@ -393,13 +402,11 @@ int spmm_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
                 err = launch_row_split_partial(a, g, reduce_size, lc, vec, rows_per_slot, (int)tile_cols, xcds, cus,
                                                c.persistent != 0, block, s);
         } else if (windows) {
-            err = launch_row_split_panels(a, g, lc, vec, rows_per_slot, par, (int)tile_cols, xcds, cus,
-                                          c.persistent != 0, block, c.long_row_min, window_bytes_of(c), workspace,
-                                          long_rows_of(c), s);
-        } else if (c.wave_rows == 1 && !par && N >= 48) {
-            // one wavefront per group_size consecutive rows, all 64 lanes on column chunks
-            const int vw = N > 128 ? vec : N > 64 ? (vec < 2 ? vec : 2) : 1;
-            err = launch_wave_rows(a, vw, group_size > 63 ? 63 : group_size, xcds, nullptr, s);
+            err = launch_row_split_panels(a, g, lc, vec, wave_vec > 0 ? wave_rows_count : rows_per_slot, par,
+                                          (int)tile_cols, xcds, cus, c.persistent != 0, block, wave_vec, c.long_row_min,
+                                          window_bytes_of(c), workspace, long_rows_of(c), s);
+        } else if (wave_vec > 0) {
+            err = launch_wave_rows(a, wave_vec, wave_rows_count, xcds, nullptr, s);
         } else {
             // the parallel strategy interleaves its groups' rows; the serial strategy's lanes
             // own consecutive rows by definition
@@ -516,6 +523,7 @@ int tune_impl(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int3
                 try_values(&sgap_config::tile_cols, {32, 64, 256});
                 if (fastest.config.strategy == SGAP_REDUCE_PARALLEL) try_values(&sgap_config::rows_per_group, {1, 2, 4, 8, 16});
                 if (fastest.config.long_row_min > 0) try_values(&sgap_config::window_kb, {2048, 4096});
+                if (fastest.config.strategy == SGAP_REDUCE_SERIAL) try_values(&sgap_config::wave_rows, {-1, 1});
             } else if (fastest.config.strategy == SGAP_REDUCE_SERIAL) {
                 try_values(&sgap_config::nnz_tile, {512, 1024, 2048});
             }

@@ -181,11 +181,12 @@ hipError_t launch_row_split_partial(const SpmmArgs& a, int g, int r, int lc, int
                                     hipStream_t s);
 // the row-split launch with rows of at least min_len stored entries taken out and
 // produced window by window of about window_bytes of B (sgap_panels.hip); vec must be 4;
+// wave_vec > 0: the other rows by launch_wave_rows with that many columns per lane and rows_per_slot rows per wavefront;
 // workspace = device memory of spmm_panels_workspace_bytes(K, N, window_bytes, cap) bytes
 // for a list of up to cap long rows (more long rows than that: the row-split kernel takes every row)
 hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
                                    int tile_cols, int xcds, int compute_units, bool persistent, int block,
-                                   int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap,
+                                   int wave_vec, int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap,
                                    hipStream_t s);
 int64_t spmm_panels_workspace_bytes(int64_t K, int64_t N, int64_t window_bytes, int64_t cap);
 int64_t sddmm_panels_workspace_bytes(int64_t K, int64_t J, int64_t window_bytes, int64_t cap);

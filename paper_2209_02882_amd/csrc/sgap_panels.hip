@@ -533,7 +533,8 @@ int64_t sddmm_panels_workspace_bytes(int64_t K, int64_t J, int64_t window_bytes,
 // bytes.  lc and the other row-split arguments as for launch_row_split.
 hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, int rows_per_slot, bool interleave,
                                    int tile_cols, int xcds, int compute_units, bool persistent, int block,
-                                   int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap, hipStream_t s)
+                                   int wave_vec, int32_t min_len, int64_t window_bytes, void* workspace, int64_t cap,
+                                   hipStream_t s)
 {
     if (vec != 4 || min_len < 1 || xcds < 1 || !workspace || cap < 1) return hipErrorInvalidValue;
     int wave_lc = 1, windows = 1;
@@ -563,9 +564,11 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
 
+    const RowSkip skip{&scr.head->count, scr.cap, min_len};
+    // serial strategy with one wavefront per rows_per_slot rows (sgap_wave_rows.hip)
+    if (wave_vec > 0) return launch_wave_rows(a, wave_vec, rows_per_slot, xcds, &skip, s);
     row_split_detail::Launch<false, true> f{a, rows_per_slot, interleave ? 1 : 0, tile_cols, xcds, compute_units,
-                                            offsets_fit_32(a), persistent, 0, block, s,
-                                            RowSkip{&scr.head->count, scr.cap, min_len}};
+                                            offsets_fit_32(a), persistent, 0, block, s, skip};
     if (!dispatch_group(g, lc, vec, f)) return hipErrorInvalidValue;
     return hipGetLastError();
 }

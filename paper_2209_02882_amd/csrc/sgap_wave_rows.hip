@@ -3,16 +3,17 @@
 // lanes of a wavefront on neighbouring column chunks (LC = 64, c = VEC columns
 // per lane), so that one wavefront owns g consecutive rows of A and one column
 // tile of 64*VEC columns of B and C.  Every lane of the wavefront then wants the
-// same stored entry, and the (column, value) pairs travel through scalar loads
-// and scalar registers (sgap_uniform.hpp): per stored entry the kernel issues one
-// scalar multiply, one buffer load and VEC multiply-adds, needs no LDS and few
-// vector registers, and a compute unit holds the most wavefronts the hardware allows.
+// same stored entry (sgap_uniform.hpp): per stored entry the kernel issues two
+// lane reads, one scalar multiply, one buffer load and VEC multiply-adds, needs
+// no LDS and few vector registers, and a compute unit holds the most wavefronts
+// the hardware allows.
 //
 // The stored entries of a wavefront's rows are contiguous in colidx/vals, so the
-// wavefront walks them D at a time without regard to row ends: D rows of B are
-// in flight whatever the row lengths are, and a row that ends inside a batch is
-// stored (plain streaming store, one owner per row: no atomics, empty rows get
-// zeros) before the next entry is added.
+// wavefront walks them in aligned runs of 64 (one coalesced load, the next run
+// requested a run ahead) and D at a time without regard to row ends: D rows of
+// B are in flight whatever the row lengths are, and a row that ends inside a
+// batch is stored (plain streaming store, one owner per row: no atomics, empty
+// rows get zeros) before the next entry is added.
 #include "sgap_common.hpp"
 #include "sgap_uniform.hpp"
 
@@ -47,9 +48,9 @@ __global__ __launch_bounds__(kBlock) void wave_rows_kernel(const int32_t* __rest
     const UniformRows<VEC, OFF32> rows(B, K, N, k_ok ? k : 0);
 
     // lane i holds rowptr[row0 + i], i <= nrows
-    const int32_t rp = rowptr[row0 + (lane <= nrows ? lane : nrows)];
     // (every lane stays active to the end: the values of rp are read across lanes below, and a lane that had
     // left would not hold its value.  Lanes past the last column work on the first chunk and store nothing.)
+    const int32_t rp = rowptr[row0 + (lane <= nrows ? lane : nrows)];
     const int32_t pend = __builtin_amdgcn_readlane(rp, nrows);
     int32_t p = __builtin_amdgcn_readlane(rp, 0);
     int row = -1;          // no row yet; the first pass of the loop below enters row 0
@@ -57,6 +58,10 @@ __global__ __launch_bounds__(kBlock) void wave_rows_kernel(const int32_t* __rest
     bool skipped = true;   // nothing to store for "row -1"
     Vec<VEC> acc;
     acc.zero();
+    // the run of 64 entries that holds position p, and the run after it
+    int32_t run = p & ~(kWave - 1);
+    EntryChunk cur = load_chunk(colidx, vals, run, pend, lane);
+    EntryChunk ahead = load_chunk(colidx, vals, run + kWave, pend, lane);
 
     auto finish_row = [&]() {
         if (!skipped && k_ok) store_vec_stream<VEC>(C + (row0 + row) * N + k, acc);
@@ -80,32 +85,34 @@ __global__ __launch_bounds__(kBlock) void wave_rows_kernel(const int32_t* __rest
             }
         }
         if (done) break;
+        if (p >= run + kWave) {
+            // on to the next run (or, past a row that was left out, to the run that holds p)
+            if (p < run + 2 * kWave) {
+                cur = ahead;
+                run += kWave;
+            } else {
+                run = p & ~(kWave - 1);
+                cur = load_chunk(colidx, vals, run, pend, lane);
+            }
+            ahead = load_chunk(colidx, vals, run + kWave, pend, lane);
+        }
 
-        // one batch: the entries p .. p + cnt - 1, whatever rows they belong to
-        const int cnt = pend - p < D ? pend - p : D;
+        // one batch: the entries p .. p + cnt - 1 of the run, whatever rows they belong to
+        const int j = p - run;
+        int cnt = pend - p < D ? pend - p : D;
+        if (kWave - j < cnt) cnt = kWave - j;
         int32_t c[D];
         float v[D];
         Vec<VEC> b[D];
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            c[u] = __builtin_amdgcn_readlane(cur.col, (j + u) & (kWave - 1));
+            v[u] = __int_as_float(__builtin_amdgcn_readlane(cur.val, (j + u) & (kWave - 1)));
+        }
         if (cnt == D) {
 #pragma unroll
-            for (int u = 0; u < D; ++u) {
-                c[u] = colidx[p + u];
-                v[u] = vals[p + u];
-            }
-#pragma unroll
-            for (int u = 0; u < D; ++u) {
-                b[u] = rows.load(c[u]);
-            }
+            for (int u = 0; u < D; ++u) b[u] = rows.load(c[u]);
         } else {
-#pragma unroll
-            for (int u = 0; u < D; ++u) {
-                c[u] = 0;
-                v[u] = 0.0f;
-                if (u < cnt) {
-                    c[u] = colidx[p + u];
-                    v[u] = vals[p + u];
-                }
-            }
 #pragma unroll
             for (int u = 0; u < D; ++u) {
                 b[u].zero();

@@ -1,6 +1,8 @@
-"""Full-size workloads in the launch configuration the benchmark times,
-checked on sampled output rows the oracle computes one by one, plus
-properties that hold at any size (no element left unwritten)."""
+"""Full-size workloads in the launch configuration the benchmark times: the
+whole result of the benchmark's best configuration and of one point of every
+other kernel family against the oracle, element by element; all 28 points on
+sampled output rows the oracle computes one by one, plus properties that hold
+at any size (no element left unwritten)."""
 import numpy as np
 import pytest
 import torch
@@ -30,6 +32,49 @@ def test_full_size_sampled_rows(name):
         got = C.index_select(0, rows_t).cpu().numpy().astype(np.float64)
         bad = np.abs(got - C_ref) > TOL * BND
         assert not bad.any(), f"{name} {point}: {int(bad.sum())} sampled elements out of tolerance"
+
+
+# the configurations bench.py ends up timing on the large workloads, and one point of each other family
+WHOLE_RESULT_CONFIGS = {
+    "stencil27": [dict(point=(1, "serial", "row_split")), dict(point=(8, "parallel", "row_split")),
+                  dict(point=(16, "serial", "nnz_balanced")), dict(point=(16, "parallel", "nnz_balanced")),
+                  dict(point=(8, "parallel", "row_split"), reduce_size=2), dict(point=(4, "serial", "row_split"), block_size=512)],
+    "rmat": [dict(point=(16, "serial", "nnz_balanced")), dict(point=(8, "parallel", "row_split")),
+             dict(point=(1, "serial", "row_split")), dict(point=(16, "parallel", "nnz_balanced")),
+             dict(point=(8, "parallel", "row_split"), long_row_min=1024), dict(point=(16, "parallel", "row_split"), reduce_size=8)],
+    "skewed": [dict(point=(1, "serial", "row_split"), long_row_min=1024, wave_rows=1),
+               dict(point=(4, "serial", "row_split"), long_row_min=1024),
+               dict(point=(4, "parallel", "row_split"), long_row_min=4096, window_kb=2048),
+               dict(point=(64, "serial", "nnz_balanced")), dict(point=(16, "parallel", "nnz_balanced")),
+               dict(point=(4, "parallel", "row_split")), dict(point=(8, "serial", "row_split"), wave_rows=1)],
+}
+
+
+@pytest.mark.parametrize("name", ["stencil27", "rmat", "skewed"])
+def test_full_size_every_element(name):
+    # the oracle does a whole large workload in well under a second per pass on 16 threads; its result and bound
+    # are taken block of rows by block of rows (a slice of the CSR arrays is a CSR matrix) to bound host memory
+    p = wl.make_problem(name)
+    dp = DeviceProblem(p)
+    outs = []
+    for spec in WHOLE_RESULT_CONFIGS[name]:
+        spec = dict(spec)
+        cfg = binding.make_config(*spec.pop("point"), **spec)
+        print("  config", binding.STRATEGY_NAMES[cfg.strategy], binding.SCHEDULE_NAMES[cfg.schedule], cfg.as_dict(), flush=True)
+        outs.append((cfg, dp.run_cfg(cfg)))
+    block = 1 << 17
+    for r0 in range(0, p.M, block):
+        r1 = min(p.M, r0 + block)
+        lo, hi = int(p.rowptr[r0]), int(p.rowptr[r1])
+        C_ref, BND = oracle.spmm_csr(r1 - r0, p.K, p.N, p.rowptr[r0:r1 + 1] - p.rowptr[r0], p.colidx[lo:hi],
+                                     p.vals[lo:hi], p.B, nthreads=16)
+        ref_t, bnd_t = torch.from_numpy(C_ref).cuda(), torch.from_numpy(BND).cuda()
+        for cfg, C in outs:
+            got = C[r0:r1].double()
+            assert not torch.isnan(got).any(), f"{name} {cfg.as_dict()}: element never written in rows {r0}..{r1}"
+            bad = (got - ref_t).abs() > TOL * bnd_t
+            assert not bool(bad.any()), f"{name} {cfg.as_dict()}: {int(bad.sum())} elements of rows {r0}..{r1} out of tolerance"
+        del ref_t, bnd_t
 
 
 @pytest.mark.parametrize("name", ["stencil27", "rmat"])

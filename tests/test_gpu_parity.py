@@ -312,6 +312,67 @@ def test_tuning_knobs_change_speed_not_results():
         binding.sgap_set_tuning(99, 1)
 
 
+def test_per_call_configuration_knobs_change_speed_not_results():
+    # the knobs of sgap_config one at a time on every point (those a point does not use are ignored)
+    p = wl.make_problem("stencil27", scale_down=64, N=128)
+    rng = np.random.default_rng(4)
+    p.vals = wl.fill_values(rng, p.nnz, True)
+    p.B = wl.fill_values(rng, p.K * p.N, True).reshape(p.K, p.N)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    knobs = [dict(block_size=v) for v in (128, 256, 512)] + [dict(tile_cols=v) for v in (4, 30, 64, 1000)]
+    knobs += [dict(rows_per_group=v) for v in (1, 3, 16)] + [dict(xcd_remap=0), dict(persistent=1)]
+    knobs += [dict(nnz_tile=v) for v in (256, 512, 2048)] + [dict(wave_rows=v) for v in (-1, 1)]
+    knobs += [dict(block_size=128, tile_cols=256, rows_per_group=2), dict(block_size=512, wave_rows=1, persistent=1)]
+    for kn in knobs:
+        for point in POINTS:
+            got = dp.run_cfg(binding.make_config(*point, **kn))
+            assert_close(got, C_ref, BND, exact=True, what=f"{kn} {ids(point)}")
+
+
+@pytest.mark.parametrize("N", [48, 64, 100, 128, 130, 256, 260, 520])
+def test_serial_row_split_with_a_wavefront_per_row(N):
+    # wave_rows = 1: the (column, value) pairs are the same for a whole wavefront; rows of every length
+    # between empty and many runs of 64 entries, every group size (rows per wavefront)
+    M, K = 1300, 3000
+    rng = np.random.default_rng(N)
+    lengths = rng.integers(0, 12, size=M)
+    lengths[3::17] = rng.integers(60, 700, size=lengths[3::17].size)
+    lengths[100:140] = 0
+    lengths[-1] = 64
+    p = csr_problem("mixed", M, K, N, lengths, seed=N, integer=True)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    for g in binding.GROUP_SIZES:
+        for block in (0, 512):  # (the layout has its own workgroup size: the knob is ignored)
+            got = dp.run_cfg(binding.make_config(g, "serial", "row_split", wave_rows=1, block_size=block))
+            assert_close(got, C_ref, BND, exact=True, what=f"N={N} g={g}")
+
+
+def test_tuner_over_the_whole_space():
+    p = wl.make_problem("skewed", scale_down=25, N=128)
+    dp = DeviceProblem(p)
+    C_ref, BND = full_reference(p)
+    probe = binding.make_config(1, "serial", "row_split", long_row_min=1024)
+    ws = dp.workspace_for(probe)
+    for workspace in (None, ws):
+        C = dp.new_output(poison=True)
+        best, table = binding.sgap_autotune_csr_cfg(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C, reps=1,
+                                                    workspace=workspace)
+        torch.cuda.synchronize()
+        assert_close(C, C_ref, BND, what="the fastest configuration's result is left in C")
+        assert len(table) >= 28 + 21 and all(t.ms > 0 for t in table)
+        assert best.ms == min(t.ms for t in table)
+        windowed = [t for t in table if t.config.long_row_min > 0]
+        assert bool(windowed) == (workspace is not None)
+        # the configuration it returns runs as it is
+        got = dp.run_cfg(best.config, workspace=workspace if best.config.long_row_min else None)
+        assert_close(got, C_ref, BND, what=f"best configuration {best.config.as_dict()}")
+    # the first 28 rated are the points of the narrow tuner, in its order
+    assert [(t.config.group_size, t.config.strategy, t.config.schedule) for t in table[:28]] == \
+        [(g, binding.STRATEGIES[st], binding.SCHEDULES[sc]) for g, st, sc in POINTS]
+
+
 @pytest.mark.parametrize("name,kw", [("uniform10", {}), ("powerlaw", dict(scale_down=8)),
                                      ("stencil27", dict(scale_down=64)), ("skewed", dict(scale_down=25, N=64)),
                                      ("uniform10", dict(N=6)), ("uniform10", dict(N=7)), ("powerlaw", dict(scale_down=8, N=4))])
