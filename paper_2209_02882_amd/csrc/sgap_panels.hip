@@ -312,7 +312,7 @@ __global__ __launch_bounds__(kBlock) void panel_rank_kernel(const int32_t* __res
 constexpr int kOwnerBlock = 1024;  // one workgroup of 16 wavefronts per compute unit
 constexpr int kOwnerWaves = kOwnerBlock / kWave;
 constexpr int kOwnerRows = 10;  // long rows a wavefront owns at a time
-constexpr int kOwnerDepth = 12;  // gathered rows of B in flight per lane
+constexpr int kOwnerDepth = 8;  // gathered rows of B in flight per lane
 
 // The same items (window, long row), but every long row has ONE owner wavefront per die, which keeps the row's
 // sums in registers while its die walks its windows and adds them into C once at the end: 8 atomic row pieces per
