@@ -17,7 +17,6 @@ from __future__ import annotations
 
 import argparse
 import glob
-import hashlib
 import json
 import os
 import sys
@@ -27,6 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+from paper_2209_02882_amd.profile_summary import kernel_source_hash  # noqa: E402
+
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate
 # Rate at which 256 compute units deliver gathered dwordx4 operands that hit in
@@ -34,18 +35,6 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate
 # (profiles/microbenchmarks.md): 55-60 bytes per clock per compute unit.
 L1_GATHER_TBS = 36.0
 LARGE_WORKLOADS = ("stencil27", "rmat", "skewed")
-
-
-def kernel_source_hash() -> str:
-    """sha256 over the kernel sources (csrc/*.hip, *.hpp, sorted by name): what a
-    measured traffic figure is tied to."""
-    h = hashlib.sha256()
-    src = os.path.join(ROOT, "paper_2209_02882_amd", "csrc")
-    for name in sorted(os.listdir(src)):
-        if name.endswith((".hip", ".hpp")):
-            h.update(name.encode())
-            h.update(open(os.path.join(src, name), "rb").read())
-    return h.hexdigest()
 
 
 def measured_traffic(op: str, workload: str, config: dict):

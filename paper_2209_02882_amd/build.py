@@ -63,5 +63,8 @@ def build_microbenchmarks() -> list[str]:
 
 
 if __name__ == "__main__":
+    import sys
+
     print(build_library())
-    print("\n".join(build_microbenchmarks()))
+    if "--microbench" in sys.argv[1:]:
+        print("\n".join(build_microbenchmarks()))
