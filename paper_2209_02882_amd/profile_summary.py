@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--config", required=True, help="JSON: the configuration as bench.py describes it")
     ap.add_argument("--out", required=True)
     ap.add_argument("--note", default="")
+    ap.add_argument("--also", action="append", default=[], metavar="RUN_DIR::CONFIG_JSON",
+                    help="a further run directory (FETCH_SIZE and WRITE_SIZE passes are enough) whose traffic record "
+                         "for another configuration of the same workload is appended")
     a = ap.parse_args()
     stats, counters, commands, bench = read_run_dir(a.run_dir)
     config = json.loads(a.config)
@@ -150,6 +153,21 @@ def main():
         if derived:
             lines += ["Derived:", ""] + derived + [""]
 
+    extra_records = []
+    for spec in a.also:
+        other_dir, other_cfg = spec.split("::", 1)
+        _, oc, ocmds, _ = read_run_dir(other_dir)
+        ok = sorted({k for k, _ in oc if not any(s_ in k for s_ in NOT_THE_CALL[1:])})
+        cp = [k for k in ok if COPY_KERNEL in k]
+        if not cp or not oc.get((cp[0], "FETCH_SIZE")) or not oc.get((cp[0], "WRITE_SIZE")):
+            raise SystemExit(f"{other_dir}: no calibrated FETCH_SIZE / WRITE_SIZE passes")
+        fs = COPY_KIB / (sum(oc[(cp[0], "FETCH_SIZE")]) / len(oc[(cp[0], "FETCH_SIZE")]))
+        ws = COPY_KIB / (sum(oc[(cp[0], "WRITE_SIZE")]) / len(oc[(cp[0], "WRITE_SIZE")]))
+        mine_o = [k for k in ok if COPY_KERNEL not in k]
+        calls_o = max((len(oc.get((k, "FETCH_SIZE"), [])) for k in mine_o), default=0)
+        tot = sum((sum(oc.get((k, "FETCH_SIZE"), [])) * fs + sum(oc.get((k, "WRITE_SIZE"), [])) * ws) * 1024 for k in mine_o)
+        extra_records.append((json.loads(other_cfg), int(round(tot / calls_o)) if calls_o else 0, ocmds))
+
     # HBM bytes per call from FETCH_SIZE / WRITE_SIZE, calibrated on the copy kernel (1 GiB in, 1 GiB out)
     record = None
     copy = [k for k in kernels if COPY_KERNEL in k]
@@ -177,6 +195,11 @@ def main():
     if record:
         lines += ["Read back by bench.py (roofline.traffic) while the kernel sources are the ones this was taken at:", "",
                   "traffic-record: " + json.dumps(record), ""]
+    for cfg, nbytes, ocmds in extra_records:
+        lines += [f"The same two counters for the configuration {json.dumps(cfg)} (commands as above with its --point): "
+                  f"{nbytes:,} bytes per call.", "",
+                  "traffic-record: " + json.dumps({"op": a.op, "workload": a.workload, "config": cfg, "bytes": nbytes,
+                                                   "source_sha256": kernel_source_hash()}), ""]
     with open(a.out, "w") as fh:
         fh.write("\n".join(lines))
     print("wrote", a.out)

@@ -277,12 +277,20 @@ def test_profile_hooks_count_main_kernels():
         binding.sgap_profile_enable(False)
 
 
-def test_copy_kernel():
-    x = torch.arange(1003 * 4 + 3, dtype=torch.float32, device="cuda:0")
+@pytest.mark.parametrize("n", [3, 1003 * 4 + 3, 4096 * 256 * 8 * 4, 4096 * 256 * 8 * 4 * 3 + 4 * 777 + 1])
+def test_stream_kernels(n):
+    # the copy moves every element (whole runs of eight accesses per lane, the rest of a workgroup's run, the last
+    # elements that do not fill 16 bytes); the write-only kernel fills; the read-only one leaves its sink alone
+    x = torch.arange(n, dtype=torch.float32, device="cuda:0")
     y = torch.zeros_like(x)
     binding.sgap_copy_f32(x, y)
     torch.cuda.synchronize()
     assert torch.equal(x, y)
+    binding.sgap_stream_f32(None, y, n, 2)
+    sink = torch.full((4,), 7.0, device="cuda:0")
+    binding.sgap_stream_f32(x, sink, n, 1)
+    torch.cuda.synchronize()
+    assert bool((y == 1.0).all()) and bool((sink == 7.0).all())
 
 
 def test_tuning_knobs_change_speed_not_results():
