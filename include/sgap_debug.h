@@ -58,14 +58,18 @@ int sgap_debug_group_seg_reduce(const float* in, const int32_t* span, float* out
  *     tiles (chunks of neighbouring tiles per die).  Writes up to `capacity`
  *     tile numbers, ascending, into out_tiles (host) and returns how many
  *     tiles the workgroup takes, or -1 on bad arguments.
- *   sgap_debug_plan_nnz_serial: tile size (stored entries) and whether a
- *     tile's partial sums are merged on chip, for the serial strategy with
- *     lanes_per_row chunk lanes of cols_per_lane columns each on a chip of
- *     compute_units; forced_tile as SGAP_TUNE_NNZ_TILE.  Host pointers.
+ *   sgap_debug_plan_nnz_serial: tile size (stored entries), whether a
+ *     tile's partial sums are merged on chip, and the chunk lanes per stored
+ *     entry the kernel runs with (lanes_per_row, or fewer where the on-chip
+ *     accumulators of a small group would not fit otherwise), for the serial
+ *     strategy with lanes_per_row chunk lanes of cols_per_lane columns each on
+ *     a chip of compute_units; forced_tile as sgap_config.nnz_tile.  Host
+ *     pointers; lanes_used may be null.
  */
 int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_tiles, int64_t capacity);
 int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
-                               int compute_units, int forced_tile, int* tile, int* merge_on_chip);
+                               int compute_units, int forced_tile, int* tile, int* merge_on_chip,
+                               int* lanes_used);
 
 /*
  * Streaming kernels over n fp32 elements (16-byte aligned device buffers):

@@ -60,7 +60,7 @@ EXPORTS = {
     "sgap_debug_group_partial_reduce": (_int, [_p, _p, _int, _int, _int, _p]),
     "sgap_debug_group_seg_reduce": (_int, [_p, _p, _p, _int, _int, _p]),
     "sgap_debug_tile_deal": (_i64, [_i64, _int, _int, _p, _i64]),
-    "sgap_debug_plan_nnz_serial": (_int, [_int, _int, _int, _i64, _int, _int, _p, _p]),
+    "sgap_debug_plan_nnz_serial": (_int, [_int, _int, _int, _i64, _int, _int, _p, _p, _p]),
     "sgap_copy_f32": (_int, [_p, _p, _i64, _p]),
     "sgap_stream_f32": (_int, [_p, _p, _i64, _int, _p]),
 }

@@ -950,7 +950,7 @@ int64_t sgap_debug_tile_deal(int64_t tiles, int grid, int block, int64_t* out_ti
 }
 
 int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_lane, int64_t nnz_hint,
-                               int compute_units_, int forced_tile, int* tile, int* merge_on_chip)
+                               int compute_units_, int forced_tile, int* tile, int* merge_on_chip, int* lanes_used)
 {
     if (!is_pow2_group(group_size) || !is_pow2_group(lanes_per_row) ||
         (cols_per_lane != 1 && cols_per_lane != 2 && cols_per_lane != 4) || compute_units_ < 1 || !tile ||
@@ -960,6 +960,7 @@ int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_l
         sgap::plan_nnz_serial(group_size, lanes_per_row, cols_per_lane, nnz_hint, compute_units_, forced_tile);
     *tile = p.tile;
     *merge_on_chip = p.merge ? 1 : 0;
+    if (lanes_used) *lanes_used = p.lc;
     return SGAP_OK;
 }
 

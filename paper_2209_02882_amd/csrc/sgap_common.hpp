@@ -156,11 +156,14 @@ __device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const Vec<
 
 // How an nnz-balanced kernel cuts the stored entries: tile = positions per LDS
 // tile, merge = tile mode of the merge rule, merge_log2 = log2 of the merge
-// block the zeroing pass must assume (tile in tile mode, group otherwise).
+// block the zeroing pass must assume (tile in tile mode, group otherwise),
+// lc = chunk lanes per stored entry the kernel is to run with (the plan may
+// narrow the layout it was asked about so that the accumulators fit the LDS).
 struct NnzPlan {
     int tile;
     bool merge;
     int merge_log2;
+    int lc;
 };
 NnzPlan plan_nnz_serial(int group, int lc, int vec, int64_t nnz_hint, int compute_units, int forced_tile);
 NnzPlan plan_nnz_parallel(int group, int lc, int vec);

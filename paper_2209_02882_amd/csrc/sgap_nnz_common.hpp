@@ -21,6 +21,12 @@ namespace sgap {
 
 constexpr int kWindowCap = 1024;              // rowptr window entries cached in LDS
 constexpr int kMergeLdsBudget = 34 * 1024;    // bytes of LDS accumulators tile mode may take
+// Small groups at wide N need one accumulator per one or two positions, far more than that budget.  Going
+// without tile mode there means a global atomic add per stored entry (or two), tens of times slower than
+// anything else in the space (Section 6.2 shows that point, its Listing 1, as the one to get away from), so
+// such points may take most of a compute unit's LDS (one workgroup per compute unit is resident then), and
+// what still does not fit runs with fewer chunk lanes per entry (more passes over the columns).
+constexpr int kMergeLdsLimit = 137 * 1024;
 constexpr int kParTile = 1024;                // positions per tile of the parallel strategy
 constexpr int kTileRowBatch = 256;            // tiles whose first rows a workgroup looks up at once
 
@@ -280,6 +286,11 @@ __device__ __forceinline__ void merge_write_out(const SpmmArgs& a, const MergeBu
 template <typename K>
 inline int resident_per_cu(K kernel, int smem)
 {
+    // more dynamic LDS than the default limit of a launch has to be asked for (once per kernel, for the
+    // most any plan takes: the tile's staging area on top of kMergeLdsLimit)
+    if (smem > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kMergeLdsLimit + 16 * 1024);
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, smem) != hipSuccess || n < 1) n = 1;
     return n;

@@ -36,6 +36,20 @@ NnzPlan plan_nnz_parallel(int group, int lc, int vec)
     p.tile = kParTile;
     const int nslots = p.tile / group + 1;
     p.merge = nslots * (lc * vec * 4 + 8) <= kMergeLdsBudget;
+    p.lc = lc;
+    // Most of the LDS, and if need be narrower passes: for G = 1 (else a global atomic add per stored entry:
+    // stencil27 32 ms against 20 ms, rmat 43 against 10) and for narrow passes (rmat, N = 32, G = 2 and 4:
+    // 23 and 10 ms against 6.0 and 3.4).  Wider passes of G >= 2 do better with their few global atomics per
+    // row than with one or two resident workgroups per compute unit (stencil27, N = 128, G = 2 and 4: 6.4 and
+    // 4.1 ms against 12.1 and 9.3; skewed, N = 256, G = 4: 30 against 39).
+    if (!p.merge && (group == 1 || lc * vec <= 32)) {
+        int lanes = lc;
+        while (nslots * (lanes * vec * 4 + 8) > kMergeLdsLimit && lanes > 1) lanes /= 2;
+        if (nslots * (lanes * vec * 4 + 8) <= kMergeLdsLimit) {
+            p.lc = lanes;
+            p.merge = true;
+        }
+    }
     int lg = 0;
     while ((1 << lg) < (p.merge ? p.tile : group)) ++lg;
     p.merge_log2 = lg;
@@ -51,6 +65,7 @@ hipError_t launch_nnz_parallel_g8_32_64(const SpmmArgs&, int, int, int, int64_t,
 hipError_t launch_nnz_parallel(const SpmmArgs& a, int lc, int vec, int compute_units, int64_t nnz_hint, hipStream_t s)
 {
     const NnzPlan plan = plan_nnz_parallel(a.group, lc, vec);
+    lc = plan.lc;
     switch (a.group) {
         case 1: return launch_nnz_parallel_g1(a, lc, vec, compute_units, nnz_hint, plan.merge, s);
         case 2: return launch_nnz_parallel_g2(a, lc, vec, compute_units, nnz_hint, plan.merge, s);

@@ -50,6 +50,22 @@ NnzPlan plan_nnz_serial(int group, int lc, int vec, int64_t nnz_hint, int comput
     if (forced_tile == 0 && vec == 4)
         while (!fits(p.tile) && p.tile / 2 >= min_tile) p.tile /= 2;
     p.merge = fits(p.tile);
+    p.lc = lc;
+    if (!p.merge && forced_tile == 0) {
+        // most of the LDS, the smallest tile this vector width has, and if need be narrower passes
+        // (against a global atomic add per flush: stencil27 G = 1 and 2 33 and 15.9 ms -> 22.9 and 6.6, rmat
+        // G = 1 44 -> 7.7, skewed G = 4 23.4 -> 13.7; skewed G = 1, whose long rows meet on one slot either
+        // way, is the one loss: 82 -> 95)
+        const int small = vec == 4 ? 256 : 1024;
+        auto fits_most = [&](int lanes) { return (small / group + 1) * (lanes * vec * 4 + 8) <= kMergeLdsLimit; };
+        int lanes = lc;
+        while (!fits_most(lanes) && lanes > 1) lanes /= 2;
+        if (fits_most(lanes)) {
+            p.tile = small;
+            p.lc = lanes;
+            p.merge = true;
+        }
+    }
     int lg = 0;
     while ((1 << lg) < (p.merge ? p.tile : group)) ++lg;
     p.merge_log2 = lg;
@@ -65,6 +81,7 @@ hipError_t launch_nnz_serial_lc64(const SpmmArgs&, int, int, int, int64_t, int, 
 hipError_t launch_nnz_serial(const SpmmArgs& a, int lc, int vec, const NnzPlan& plan, int compute_units,
                              int64_t nnz_hint, hipStream_t s)
 {
+    lc = plan.lc;  // the plan may have narrowed the layout
     switch (lc) {
         case 1: case 2: return launch_nnz_serial_lc1_2(a, lc, vec, compute_units, nnz_hint, plan.tile, plan.merge, s);
         case 4: case 8: return launch_nnz_serial_lc4_8(a, lc, vec, compute_units, nnz_hint, plan.tile, plan.merge, s);

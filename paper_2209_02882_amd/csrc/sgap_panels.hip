@@ -77,36 +77,74 @@ __global__ void panel_reset_kernel(PanelView scr)
     if (blockIdx.x == 0 && threadIdx.x < 16) (&scr.head->count)[threadIdx.x] = 0;  // count and next[]
 }
 
+// A workgroup looks at kFindRows rows per thread and adds to the list's counter once: a returning atomic on one
+// address takes about 0.1 us (they are carried out one after another, beyond the dies' L2s), and a matrix may have
+// thousands of long rows (skewed, 5,000 of them: 44 us with one update per wavefront that found a row).
+constexpr int kFindRows = 8;
 __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, PanelView scr, int32_t min_len)
 {
-    const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const bool is_long = row < a.M && a.rowptr[row + 1] - a.rowptr[row] >= min_len;
-    // one counter update per wavefront: a returning atomic on one address takes about 0.1 us,
-    // and a matrix may have thousands of long rows
-    const unsigned long long mask = __ballot(is_long);
-    if (mask == 0) return;
+    __shared__ uint32_t s_wave[kWavesPerBlock];
+    __shared__ uint32_t s_base;
     const int lane = threadIdx.x % kWave;
-    uint32_t base = 0;
-    if (lane == __ffsll((long long)mask) - 1) base = atomicAdd(&scr.head->count, (uint32_t)__popcll(mask));
-    base = (uint32_t)__shfl((int)base, __ffsll((long long)mask) - 1, kWave);
-    if (is_long) {
-        const uint32_t i = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (i < scr.cap) scr.rows[i] = (int32_t)row;
+    const int wave = threadIdx.x / kWave;
+    const int64_t row0 = (int64_t)blockIdx.x * (kBlock * kFindRows) + threadIdx.x;
+    uint32_t mine = 0;  // bit j: row row0 + j * kBlock is long
+#pragma unroll
+    for (int j = 0; j < kFindRows; ++j) {
+        const int64_t row = row0 + (int64_t)j * kBlock;
+        if (row < a.M && a.rowptr[row + 1] - a.rowptr[row] >= min_len) mine |= 1u << j;
+    }
+    const uint32_t cnt = (uint32_t)__popc(mine);
+    uint32_t incl = cnt;  // long rows of this and the lower lanes of the wavefront
+#pragma unroll
+    for (int d = 1; d < kWave; d *= 2) {
+        const uint32_t t = (uint32_t)__shfl_up((int)incl, d, kWave);
+        if (lane >= d) incl += t;
+    }
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const uint32_t c = s_wave[w];
+            s_wave[w] = total;
+            total += c;
+        }
+        s_base = total ? atomicAdd(&scr.head->count, total) : 0u;
+    }
+    __syncthreads();
+    uint32_t i = s_base + s_wave[wave] + incl - cnt;
+#pragma unroll
+    for (int j = 0; j < kFindRows; ++j) {
+        if (!(mine & (1u << j))) continue;
+        if (i < scr.cap) scr.rows[i] = (int32_t)(row0 + (int64_t)j * kBlock);
+        ++i;
     }
 }
 
-// Window pointers of the long rows, and (zero_rows) zeros in their rows of C.
+// Window pointers of the long rows, and (zero_rows) zeros in their rows of C.  A list of at least `few_from`
+// rows is panel_owner_kernel's, which finds the windows' ends itself while it walks a row and needs only the
+// pointers of the first window of every die's share (and the row's end): those alone are written then.
+__device__ __forceinline__ int panel_share_begin(int xcd, int windows, int xcds)
+{
+    return (int)((int64_t)xcd * windows / xcds);  // die x walks the windows [begin(x), begin(x + 1))
+}
+
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelView scr, int windows,
-                                                                int32_t window_rows, int zero_rows)
+                                                                int32_t window_rows, int zero_rows, uint32_t few_from,
+                                                                int xcds)
 {
     const uint32_t n = scr.head->count;
     if (n == 0 || n > scr.cap) return;
     const int64_t threads = (int64_t)gridDim.x * kBlock;
     const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int per_row = windows + 1;
-    for (int64_t t = tid; t < (int64_t)n * per_row; t += threads) {
-        const int i = (int)(t / per_row), w = (int)(t % per_row);
+    const bool few = n >= few_from;
+    const int wanted = few ? xcds + 1 : per_row;
+    for (int64_t t = tid; t < (int64_t)n * wanted; t += threads) {
+        const int i = (int)(t / wanted);
+        const int w = few ? panel_share_begin((int)(t % wanted), windows, xcds) : (int)(t % wanted);
         const int32_t row = scr.rows[i];
         int32_t lo = a.rowptr[row], hi = a.rowptr[row + 1];
         if (w < windows) {
@@ -123,7 +161,7 @@ __global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, Pane
             lo = hi;
         }
         scr.ptr[(int64_t)i * per_row + w] = lo;
-        if (w == 0) scr.order[i] = i;  // until panel_rank_kernel sorts the list
+        if (t % wanted == 0) scr.order[i] = i;  // until panel_rank_kernel sorts the list
     }
     if (!zero_rows) return;
     const int64_t chunks = a.N / VEC;  // N % VEC == 0
@@ -314,25 +352,31 @@ constexpr int kOwnerWaves = kOwnerBlock / kWave;
 constexpr int kOwnerRows = 10;  // long rows a wavefront owns at a time
 constexpr int kOwnerDepth = 8;  // gathered rows of B in flight per lane
 
-// The same items (window, long row), but every long row has ONE owner wavefront per die, which keeps the row's
+// The same work (window, long row), but every long row has ONE owner wavefront per die, which keeps the row's
 // sums in registers while its die walks its windows and adds them into C once at the end: 8 atomic row pieces per
-// long row instead of one per window.  A die's wavefronts each own up to kOwnerRows rows (more rows: more passes)
-// and take window after window in the same order, so that at any moment they gather from one or two windows,
-// which the die's L2 holds.  Two things keep them in step.  Rows are dealt from the longest to the shortest, back
-// and forth over the wavefronts, so that all have about the same number of entries per window.  And a compute
-// unit runs one workgroup of 16 wavefronts that meet at a barrier after every window: the hardware issues the
-// memory instructions of the oldest wavefronts of a compute unit first, and without the barrier the youngest end
-// up 1.5 times slower and sixteen windows behind (measured), far more than an L2 holds.  Between compute units
-// nothing but their equal shares of the work keeps the pace: they are alike, and each averages over 160 rows.
+// long row instead of one per window.  A die's share is a run of consecutive windows, so that its part of a row
+// is one run of stored entries: a wavefront keeps a position per row, takes from there what lies in front of
+// the current window's last column, and stays there until the next window (no pointer per window is needed, only
+// the share's ends).  A die's wavefronts each own up to kOwnerRows rows (more rows: more passes) and take window
+// after window in the same order, so that at any moment they gather from one or two windows, which the die's L2
+// holds.  Two things keep them in step.  Rows are dealt from the longest to the shortest, back and forth over the
+// wavefronts, so that all have about the same number of entries per window.  And a compute unit runs one
+// workgroup of 16 wavefronts that meet at a barrier after every window: the hardware issues the memory
+// instructions of the oldest wavefronts of a compute unit first, and without the barrier the youngest end up 1.5
+// times slower and sixteen windows behind (measured), far more than an L2 holds.  Between compute units nothing
+// but their equal shares of the work keeps the pace: they are alike, and each averages over 160 rows.
 // One wavefront per row and 64 lanes on 64 column chunks: the entries are wave-uniform (sgap_uniform.hpp).
+// Nothing here relies on sorted columns: an entry is taken in the first window of the share at which it is at
+// the front of what is left and lies in front of the window's end, at the latest in the share's last window,
+// which takes all that is left.
 // Runs only when the list holds at least min_rows rows; with fewer, most wavefronts would own nothing and
 // panel_long_rows_kernel (which then runs instead) keeps the whole chip busy.
 template <int VEC, bool OFF32>
 __global__ __launch_bounds__(kOwnerBlock) void panel_owner_kernel(const int32_t* __restrict__ colidx,
                                                                   const float* __restrict__ vals,
                                                                   const float* __restrict__ B, float* __restrict__ C,
-                                                                  PanelView scr, int64_t K,
-                                                                  int64_t N, int windows, int xcds, uint32_t min_rows)
+                                                                  PanelView scr, int64_t K, int64_t N, int windows,
+                                                                  int32_t window_rows, int xcds, uint32_t min_rows)
 {
     constexpr int R = kOwnerRows;
     const uint32_t n = scr.head->count;
@@ -344,6 +388,8 @@ __global__ __launch_bounds__(kOwnerBlock) void panel_owner_kernel(const int32_t*
     const uint32_t me = (blockIdx.x / xcds) * kOwnerWaves + wave;
     const uint32_t rounds = (n + waves - 1) / waves;           // rows a wavefront owns in all
     const int per_row = windows + 1;
+    const int w_begin = panel_share_begin((int)xcd, windows, xcds);
+    const int w_end = panel_share_begin((int)xcd + 1, windows, xcds);
     const int tiles = (int)((N + kWave * VEC - 1) / (kWave * VEC));
     SpmmArgs a;  // what panel_flush needs
     a.N = N;
@@ -354,53 +400,63 @@ __global__ __launch_bounds__(kOwnerBlock) void panel_owner_kernel(const int32_t*
         const bool k_ok = k < N;
         const UniformRows<VEC, OFF32> rows(B, K, N, k_ok ? k : 0);
         for (uint32_t r0 = 0; r0 < rounds; r0 += R) {
-            // lane l < 2R looks after one number per window: the first (l < R) or the end (l >= R) position
-            // of the entries of row slot l % R in that window; lane l < R also knows the slot's row.
+            // lane l < 3R looks after one position of row slot l % R: where the slot's next entry is (l < R),
+            // where the die's share of the row ends (R <= l < 2R), where the 64 entries start that the wavefront
+            // holds of the row (2R <= l < 3R); lane l < R also knows the slot's row.
             // (A wavefront without rows in this pass walks along with nothing to do: it is needed at the barriers.)
-            int64_t my_ptr = -1;
+            int32_t my_pos = 0;
             int32_t my_row = -1;
             {
                 const uint32_t round = r0 + (uint32_t)(lane % R);
                 const uint32_t q = round * waves + ((round & 1u) ? waves - 1u - me : me);
-                if (lane < 2 * R && round < rounds && q < n) {
+                if (lane < 3 * R && round < rounds && q < n) {
                     const int32_t i = scr.order[q];
-                    my_ptr = (int64_t)i * per_row + lane / R;
+                    my_pos = scr.ptr[(int64_t)i * per_row + (lane >= R && lane < 2 * R ? w_end : w_begin)];
                     my_row = scr.rows[i];
                 }
             }
             Vec<VEC> acc[R];
+            // 64 entries of every row slot stay in registers from window to window: a window ends somewhere
+            // inside them, and the rest is the start of the slot's piece in the next window
+            EntryChunk held[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) acc[r].zero();
-            // The pieces (window, row slot) come in a fixed order, and the first 64 entries of a piece are
-            // requested while the piece before it is multiplied out (as are the next 64 of a longer piece).
-            int32_t next_bound = my_ptr >= 0 && (int)xcd < windows ? scr.ptr[my_ptr + xcd] : 0;
-            EntryChunk cur = load_chunk(colidx, vals, __builtin_amdgcn_readlane(next_bound, 0),
-                                        __builtin_amdgcn_readlane(next_bound, R), lane);
-            for (int w = (int)xcd; w < windows; w += xcds) {
-                const int32_t bound = next_bound;
-                next_bound = my_ptr >= 0 && w + xcds < windows ? scr.ptr[my_ptr + w + xcds] : 0;
+            for (int r = 0; r < R; ++r) {
+                acc[r].zero();
+                held[r] = load_chunk(colidx, vals, __builtin_amdgcn_readlane(my_pos, r),
+                                     __builtin_amdgcn_readlane(my_pos, R + r), lane);
+            }
+            for (int w = w_begin; w < w_end; ++w) {
+                const bool last = w + 1 == w_end;  // of the share: takes all that is left
+                const int64_t limit64 = (int64_t)(w + 1) * window_rows;
+                const int32_t limit = limit64 > 0x7fffffffLL ? 0x7fffffff : (int32_t)limit64;
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const int32_t p0 = __builtin_amdgcn_readlane(bound, r);
-                    const int32_t p1 = __builtin_amdgcn_readlane(bound, R + r);
-                    // the piece after this one
-                    const int32_t np0 = r + 1 < R ? __builtin_amdgcn_readlane(bound, (r + 1) % R)
-                                                  : __builtin_amdgcn_readlane(next_bound, 0);
-                    const int32_t np1 = r + 1 < R ? __builtin_amdgcn_readlane(bound, R + (r + 1) % R)
-                                                  : __builtin_amdgcn_readlane(next_bound, R);
-                    if (p0 >= p1) {
-                        // nothing here (and nothing was requested for it)
-                        cur = load_chunk(colidx, vals, np0, np1, lane);
-                        continue;
+                    int32_t p = __builtin_amdgcn_readlane(my_pos, r);
+                    const int32_t end = __builtin_amdgcn_readlane(my_pos, R + r);
+                    int32_t base = __builtin_amdgcn_readlane(my_pos, 2 * R + r);
+                    for (;;) {
+                        // held[r] has the entries base .. base + 63 (none at or beyond end); p lies among them
+                        const int from = p - base;
+                        int to = end - base < kWave ? end - base : kWave;
+                        if (to < from) to = from;
+                        const bool whole = to == kWave && base + kWave < end;  // the row goes on behind them
+                        if (!last) {
+                            const unsigned long long beyond =
+                                __ballot(lane >= from && lane < to && held[r].col >= limit);
+                            if (beyond) to = __ffsll((long long)beyond) - 1;
+                        }
+                        // all of them taken and more to come: the next 64 are requested before these are multiplied
+                        const bool refill = whole && to == kWave;
+                        EntryChunk ahead = held[r];
+                        if (refill) ahead = load_chunk(colidx, vals, base + kWave, end, lane);
+                        if (to > from) chunk_accumulate<VEC, OFF32, kOwnerDepth>(rows, acc[r], held[r], from, to);
+                        p = base + to;
+                        if (!refill) break;
+                        held[r] = ahead;
+                        base += kWave;
                     }
-                    for (int32_t base = p0; base < p1; base += kWave) {
-                        const int32_t after = base + kWave;
-                        const EntryChunk ahead = after < p1 ? load_chunk(colidx, vals, after, p1, lane)
-                                                            : load_chunk(colidx, vals, np0, np1, lane);
-                        const int cnt = p1 - base < kWave ? p1 - base : kWave;
-                        chunk_accumulate<VEC, OFF32, kOwnerDepth>(rows, acc[r], cur, 0, cnt);
-                        cur = ahead;
-                    }
+                    if (lane == r) my_pos = p;
+                    if (lane == 2 * R + r) my_pos = base;
                 }
                 __syncthreads();  // the compute unit's wavefronts take the next window together
             }
@@ -443,25 +499,32 @@ void launch_long_rows(const SpmmArgs& a, const PanelView& scr, int windows, int 
                            xcds, below);
 }
 
-// The owner kernel for lists of at least *min_rows rows (half the wavefronts of a die: with fewer rows than that
-// most wavefronts would own nothing); returns that threshold so that the claiming kernel can stand back.
+// The owner kernel runs for lists of at least owner_min_rows rows (half the wavefronts of a die: with fewer rows
+// than that most wavefronts would own nothing); below that the claiming kernel does.
+uint32_t owner_min_rows(int xcds, int compute_units)
+{
+    int grid = compute_units;
+    grid -= grid % xcds;
+    if (grid < xcds) grid = xcds;
+    return (uint32_t)(grid / xcds) * kOwnerWaves / 2;
+}
+
 template <int VEC>
-uint32_t launch_owner_rows(const SpmmArgs& a, const PanelView& scr, int windows, int xcds, int compute_units,
-                           hipStream_t s)
+void launch_owner_rows(const SpmmArgs& a, const PanelView& scr, int windows, int32_t window_rows, int xcds,
+                       int compute_units, hipStream_t s)
 {
     const bool off32 = offsets_fit_32(a);
     // one workgroup per compute unit (nothing depends on their all being resident: there is no waiting between them)
     int grid = compute_units;
     grid -= grid % xcds;
     if (grid < xcds) grid = xcds;
-    const uint32_t min_rows = (uint32_t)(grid / xcds) * kOwnerWaves / 2;
+    const uint32_t min_rows = owner_min_rows(xcds, compute_units);
     if (off32)
         hipLaunchKernelGGL((panel_owner_kernel<VEC, true>), dim3(grid), dim3(kOwnerBlock), 0, s, a.colidx, a.vals, a.B,
-                           a.C, scr, a.K, a.N, windows, xcds, min_rows);
+                           a.C, scr, a.K, a.N, windows, window_rows, xcds, min_rows);
     else
         hipLaunchKernelGGL((panel_owner_kernel<VEC, false>), dim3(grid), dim3(kOwnerBlock), 0, s, a.colidx, a.vals, a.B,
-                           a.C, scr, a.K, a.N, windows, xcds, min_rows);
-    return min_rows;
+                           a.C, scr, a.K, a.N, windows, window_rows, xcds, min_rows);
 }
 
 // Column windows of about window_bytes of B each, at most kPanelMaxWindows.
@@ -482,14 +545,20 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
 
 // The preparation both operators share: list of the rows of at least min_len
 // entries, their window pointers, and (zero_rows) zeros in their rows of C.
+// owners: the list goes to panel_owner_kernel when it is long enough (the rows are ranked for it, and
+// it needs the pointers of its xcds shares only).
 void launch_panel_preparation(const SpmmArgs& a, const PanelView& scr, int windows, int32_t window_rows,
-                              int32_t min_len, bool zero_rows, bool rank_rows, int compute_units, hipStream_t s)
+                              int32_t min_len, bool zero_rows, bool owners, int xcds, int compute_units,
+                              hipStream_t s)
 {
+    const bool rank_rows = owners;
+    const uint32_t few_from = owners ? owner_min_rows(xcds, compute_units) : 0xffffffffu;
     hipLaunchKernelGGL(panel_reset_kernel, dim3(1), dim3(kWave), 0, s, scr);
-    hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, scr,
-                       min_len);
+    constexpr int64_t rows_per_block = (int64_t)kBlock * kFindRows;
+    hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + rows_per_block - 1) / rows_per_block)), dim3(kBlock),
+                       0, s, a, scr, min_len);
     hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, windows,
-                       window_rows, zero_rows ? 1 : 0);
+                       window_rows, zero_rows ? 1 : 0, few_from, xcds);
     if (rank_rows) {
         const uint32_t rows = scr.cap < (uint32_t)kRankMaxRows ? scr.cap : (uint32_t)kRankMaxRows;
         hipLaunchKernelGGL(panel_rank_kernel, dim3((rows + kBlock / kRankLanes - 1) / (kBlock / kRankLanes)), dim3(kBlock),
@@ -549,9 +618,12 @@ hipError_t launch_row_split_panels(const SpmmArgs& a, int g, int lc, int vec, in
     const PanelView scr = panel_view(workspace, cap, windows);
     // a wavefront per row with all 64 lanes on column chunks: worth it from 128 columns on
     const bool owners = wave_lc == kPanelTileLanes && a.N >= 128;
-    launch_panel_preparation(a, scr, windows, window_rows, min_len, true, owners, compute_units, s);
+    launch_panel_preparation(a, scr, windows, window_rows, min_len, true, owners, xcds, compute_units, s);
     uint32_t below = 0xffffffffu;
-    if (owners) below = launch_owner_rows<4>(a, scr, windows, xcds, compute_units, s);
+    if (owners) {
+        launch_owner_rows<4>(a, scr, windows, window_rows, xcds, compute_units, s);
+        below = owner_min_rows(xcds, compute_units);
+    }
     switch (wave_lc) {
         case 1: launch_long_rows<64, 1, 4>(a, scr, windows, xcds, compute_units, below, s); break;
         case 2: launch_long_rows<32, 2, 4>(a, scr, windows, xcds, compute_units, below, s); break;
@@ -733,7 +805,7 @@ hipError_t launch_sddmm_panels(const SpmmArgs& a, const float* X1, float* out, i
     plan_panels(a.K, a.N, window_bytes, &windows, &window_rows);
     if ((int64_t)windows * cap > 0xffffffffLL) return hipErrorInvalidValue;
     const PanelView scr = panel_view(workspace, cap, windows);
-    launch_panel_preparation(a, scr, windows, window_rows, min_len, false, false, compute_units, s);
+    launch_panel_preparation(a, scr, windows, window_rows, min_len, false, false, 1, compute_units, s);
     int wave_lc = 8;
     while (wave_lc < kWave && (int64_t)wave_lc * 4 < a.N) wave_lc *= 2;
     switch (wave_lc) {

@@ -69,13 +69,17 @@ def read_run_dir(run_dir):
     return stats, counters, commands, bench
 
 
+SHAPE_KEYS = ("workload", "M", "K", "N", "nnz", "J", "rank")  # what bench.py adds to a configuration's description
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("run_dir")
     ap.add_argument("--title", required=True)
     ap.add_argument("--op", default="spmm")
-    ap.add_argument("--workload", required=True)
-    ap.add_argument("--config", required=True, help="JSON: the configuration as bench.py describes it")
+    ap.add_argument("--workload", default=None, help="default: the one the run's bench.py line names")
+    ap.add_argument("--config", default=None,
+                    help="JSON: the configuration as bench.py describes it (default: the one of the run's bench.py line)")
     ap.add_argument("--out", required=True)
     ap.add_argument("--note", default="")
     ap.add_argument("--also", action="append", default=[], metavar="RUN_DIR::CONFIG_JSON",
@@ -83,7 +87,14 @@ def main():
                          "for another configuration of the same workload is appended")
     a = ap.parse_args()
     stats, counters, commands, bench = read_run_dir(a.run_dir)
-    config = json.loads(a.config)
+    named = dict(bench.get("config", {})) if bench else {}
+    if a.workload is None:
+        a.workload = named.get("workload")
+    for shape in SHAPE_KEYS:
+        named.pop(shape, None)
+    config = json.loads(a.config) if a.config else named
+    if not a.workload or not config:
+        ap.error("the run holds no bench.py line: give --workload and --config")
 
     lines = [f"# {a.title}", ""]
     if a.note:

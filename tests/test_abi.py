@@ -280,15 +280,25 @@ def test_serial_plan_keeps_partial_sums_on_chip_and_fills_the_chip():
     lib = binding.load()
 
     def plan(g, lc, vec, nnz, cus=256, forced=0):
-        tile, merge = ctypes.c_int(), ctypes.c_int()
-        assert lib.sgap_debug_plan_nnz_serial(g, lc, vec, nnz, cus, forced, ctypes.byref(tile), ctypes.byref(merge)) == 0
+        tile, merge, lanes = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        assert lib.sgap_debug_plan_nnz_serial(g, lc, vec, nnz, cus, forced, ctypes.byref(tile), ctypes.byref(merge),
+                                              ctypes.byref(lanes)) == 0
+        used.append(lanes.value)
         return tile.value, bool(merge.value)
+
+    used = []
 
     # large matrices: 1024 or 2048 entries, shrunk until the slots fit 34 KB
     assert plan(32, 8, 4, 50_000_000) == (1024, True)
     assert plan(64, 1, 4, 50_000_000) == (2048, True)
     assert plan(8, 32, 4, 26_000_000) == (512, True)      # 128 columns: 65 slots of 520 bytes
-    assert plan(2, 32, 4, 26_000_000) == (256, False)     # does not fit even at 256: global atomics
+    assert used[-1] == 32
+    # small groups at wide N: most of the LDS at the smallest tile (129 slots of 520 bytes) ...
+    assert plan(2, 32, 4, 26_000_000) == (256, True) and used[-1] == 32
+    # ... and fewer chunk lanes per entry where even that is too little (257 slots: 1032 bytes each do not fit, 520 do)
+    assert plan(1, 64, 4, 57_000_000) == (256, True) and used[-1] == 32
+    assert plan(1, 64, 1, 57_000_000) == (1024, True) and used[-1] == 32   # 1025 slots of 136 bytes
+    assert plan(2, 32, 4, 26_000_000, forced=256) == (256, False)          # a forced tile keeps the plain rule
     # small matrices: smaller tiles so that the chip's ~1024 resident workgroups all get work
     assert plan(16, 8, 4, 10_240)[0] == 256
     assert plan(16, 16, 4, 1_053_925)[0] in (256, 512)
@@ -296,7 +306,7 @@ def test_serial_plan_keeps_partial_sums_on_chip_and_fills_the_chip():
     assert plan(16, 8, 4, -1)[0] == 1024
     assert plan(16, 8, 2, 10_240)[0] == 1024
     assert plan(16, 8, 4, 10_240, forced=2048)[0] == 2048
-    assert lib.sgap_debug_plan_nnz_serial(3, 8, 4, 0, 256, 0, None, None) == binding.SGAP_ERR_INVALID_ARG
+    assert lib.sgap_debug_plan_nnz_serial(3, 8, 4, 0, 256, 0, None, None, None) == binding.SGAP_ERR_INVALID_ARG
 
 
 def test_header_is_plain_c_and_links_against_the_library(tmp_path):
