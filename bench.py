@@ -459,6 +459,32 @@ def candidates(p, binding, with_gr):
     return out
 
 
+def reordered_rows(dp, torch, binding, C, cfg, ws, cfg_d):
+    """The same configuration on the copies of the matrix that sgap_reorder_rows_csr writes (rows grouped by
+    first column, by length): time of the pass and of a call on the copy, whose product has its rows in the
+    new order.  An option a caller has, not part of the headline."""
+    import copy
+
+    p = dp.p
+    dev = dp.rowptr.device
+    perm = torch.empty(p.M, dtype=torch.int32, device=dev)
+    rowptr = torch.empty_like(dp.rowptr)
+    colidx = torch.empty_like(dp.colidx)
+    vals = torch.empty_like(dp.vals)
+    order_ws = torch.empty(binding.sgap_reorder_rows_workspace_size(p.M), dtype=torch.uint8, device=dev)
+    out = []
+    for order in ("first_column", "length"):
+        run = lambda: binding.sgap_reorder_rows_csr(p.M, p.K, dp.rowptr, dp.colidx, dp.vals, order, perm, rowptr,
+                                                    colidx, vals, order_ws)
+        pre = launch_stats(torch, run, 5)
+        dq = copy.copy(dp)
+        dq.rowptr, dq.colidx, dq.vals = rowptr, colidx, vals
+        t = time_config(dq, torch, C, cfg, ws, 20)
+        out.append({"order": order, "preprocessing_ms": pre["median"], "ms_per_step": t * 1e3, "config": cfg_d})
+        log(f"[bench] {p.name}: rows by {order}: pass {pre['median']:.3f} ms, call {t * 1e3:.3f} ms")
+    return out
+
+
 def measure_spmm(a, name, torch, binding, wl, copy_gbs):
     """Sweep, time and rate one workload; returns its record of the JSON line."""
     from paper_2209_02882_amd.device import DeviceProblem
@@ -540,6 +566,8 @@ def measure_spmm(a, name, torch, binding, wl, copy_gbs):
             "algorithmic_bytes": min_bytes,
         },
     }
+    if not a.no_reorder and not a.point:
+        rec["reordered_rows"] = reordered_rows(dp, torch, binding, C, best, ws, best_d)
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(p, a.cpu_seconds)
     if a.sweep_out and sweep:
@@ -555,6 +583,8 @@ def main():
     ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm", "mttkrp", "ttm"),
                     help="spmm (the headline path), sddmm on the same workload's pattern, or mttkrp / ttm on a "
                          "seeded third-order tensor")
+    ap.add_argument("--no-reorder", action="store_true",
+                    help="skip the leg that times the best configuration on the reordered copies of the matrix")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)

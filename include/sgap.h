@@ -564,6 +564,41 @@ int sgap_set_tuning(int knob, int value);
 int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, int64_t nnz,
                       int64_t* report, void* stream);
 
+/*
+ * Row order for locality (optional preprocessing; the schedules of Section 6
+ * take the rows in the order in which they are stored, and Section 2.2 names
+ * the work on locality that a better order stands for).  Writes a copy of the
+ * CSR matrix whose rows are grouped by a coarse key, smaller key first, rows of
+ * equal key in no particular order:
+ *   SGAP_ORDER_BY_FIRST_COLUMN  key = floor(first stored column * 4096 / K);
+ *                               rows without stored entries last (key 4096)
+ *   SGAP_ORDER_BY_LENGTH        key = 4096 - min(stored entries, 4096): the
+ *                               longest rows first, rows without entries last
+ * The stored entries of a row keep their order.  The product of the new
+ * matrix comes out in the new row order: row j of A' * B is row perm[j] of
+ * A * B.
+ *   rowptr, colidx, vals   device, the matrix as for sgap_spmm_csr; read only
+ *   perm                   device, M: perm[j] = the row of A that is row j of A'
+ *   rowptr_out             device, M+1
+ *   colidx_out, vals_out   device, nnz = rowptr[M] each; must not overlap the inputs
+ *                          (these two and colidx, vals may be null only when
+ *                          the matrix has no stored entries: the host cannot check)
+ *   workspace              device, at least sgap_reorder_rows_workspace_size(M)
+ *                          bytes, 16-byte aligned, caller-owned, contents
+ *                          meaningless before and after; calls that overlap in
+ *                          time need a workspace each
+ * Asynchronous on `stream`; allocates nothing.  M == 0 writes rowptr_out[0] = 0.
+ * Errors: SGAP_ERR_INVALID_ARG (negative sizes, M beyond the int32 row range,
+ * K < 1 with M > 0, unknown order, null rowptr, rowptr_out or perm, workspace
+ * too small or misaligned) launches nothing; SGAP_ERR_HIP as for the compute calls.
+ * sgap_reorder_rows_workspace_size returns -1 for a negative M.
+ */
+typedef enum { SGAP_ORDER_BY_FIRST_COLUMN = 0, SGAP_ORDER_BY_LENGTH = 1 } sgap_row_order;
+int64_t sgap_reorder_rows_workspace_size(int64_t M);
+int sgap_reorder_rows_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                          int order, int32_t* perm, int32_t* rowptr_out, int32_t* colidx_out, float* vals_out,
+                          void* workspace, int64_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

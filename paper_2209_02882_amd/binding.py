@@ -48,6 +48,8 @@ EXPORTS = {
                                       _i64, _p]),
     "sgap_sddmm_csr_workspace_size": (_i64, [_i64, _i64, _int, _int]),
     "sgap_validate_csr": (_int, [_i64, _i64, _p, _p, _i64, _p, _p]),
+    "sgap_reorder_rows_workspace_size": (_i64, [_i64]),
+    "sgap_reorder_rows_csr": (_int, [_i64, _i64, _p, _p, _p, _int, _p, _p, _p, _p, _p, _i64, _p]),
     "sgap_ttm_csf": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_mttkrp_csf": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
@@ -344,6 +346,38 @@ def sgap_validate_csr(M, K, rowptr, colidx, stream=None):
                                     _dev_ptr(colidx, torch.int32, "colidx"), colidx.numel(), report,
                                     _stream_ptr(stream)))
     return tuple(report)
+
+
+ROW_ORDERS = {"first_column": 0, "length": 1}
+
+
+def sgap_reorder_rows_workspace_size(M):
+    size = load().sgap_reorder_rows_workspace_size(M)
+    if size < 0:
+        raise SgapError(SGAP_ERR_INVALID_ARG, load().sgap_last_error().decode())
+    return size
+
+
+def sgap_reorder_rows_csr(M, K, rowptr, colidx, vals, order, perm, rowptr_out, colidx_out, vals_out, workspace,
+                          stream=None):
+    """Enqueue the row reordering of a CSR matrix in device memory (see include/sgap.h); `order` is a name of
+    ROW_ORDERS or its number.  All arrays are the caller's tensors; nothing is allocated here."""
+    import torch
+
+    if rowptr.numel() != M + 1 or rowptr_out.numel() != M + 1:
+        raise ValueError("rowptr and rowptr_out must have M+1 entries")
+    if perm.numel() != M:
+        raise ValueError("perm must have M entries")
+    if colidx_out.numel() != colidx.numel() or vals_out.numel() != vals.numel() or vals.numel() != colidx.numel():
+        raise ValueError("colidx, vals and their outputs must have nnz entries each")
+    ws_ptr, ws_bytes = _workspace_args(workspace)
+    _check(load().sgap_reorder_rows_csr(M, K, _dev_ptr(rowptr, torch.int32, "rowptr"),
+                                        _dev_ptr(colidx, torch.int32, "colidx"), _dev_ptr(vals, torch.float32, "vals"),
+                                        ROW_ORDERS.get(order, order), _dev_ptr(perm, torch.int32, "perm"),
+                                        _dev_ptr(rowptr_out, torch.int32, "rowptr_out"),
+                                        _dev_ptr(colidx_out, torch.int32, "colidx_out"),
+                                        _dev_ptr(vals_out, torch.float32, "vals_out"), ws_ptr, ws_bytes,
+                                        _stream_ptr(stream)))
 
 
 class PointTime(ctypes.Structure):

@@ -964,6 +964,44 @@ int sgap_debug_plan_nnz_serial(int group_size, int lanes_per_row, int cols_per_l
     return SGAP_OK;
 }
 
+int64_t sgap_reorder_rows_workspace_size(int64_t M)
+{
+    if (M < 0) {
+        fail(SGAP_ERR_INVALID_ARG, "negative size");
+        return -1;
+    }
+    return sgap::reorder_workspace_bytes(M);
+}
+
+__global__ void first_rowptr_kernel(int32_t* rowptr_out) { rowptr_out[0] = 0; }
+
+int sgap_reorder_rows_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                          int order, int32_t* perm, int32_t* rowptr_out, int32_t* colidx_out, float* vals_out,
+                          void* workspace, int64_t workspace_bytes, void* stream)
+{
+    using namespace sgap;
+    if (M < 0 || K < 0) return fail(SGAP_ERR_INVALID_ARG, "negative size");
+    if (M > 2147483646LL) return fail(SGAP_ERR_INVALID_ARG, "M exceeds the int32 row range");
+    if (order != SGAP_ORDER_BY_FIRST_COLUMN && order != SGAP_ORDER_BY_LENGTH)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown row order");
+    if (!rowptr || !rowptr_out) return fail(SGAP_ERR_INVALID_ARG, "rowptr and rowptr_out must not be null");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (M == 0) {
+        hipLaunchKernelGGL(first_rowptr_kernel, dim3(1), dim3(1), 0, s, rowptr_out);
+        const hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(e0));
+        return SGAP_OK;
+    }
+    if (K < 1) return fail(SGAP_ERR_INVALID_ARG, "K must be positive when the matrix has rows");
+    if (!perm) return fail(SGAP_ERR_INVALID_ARG, "perm must not be null");
+    if (!workspace || workspace_bytes < reorder_workspace_bytes(M) || (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return fail(SGAP_ERR_INVALID_ARG, "workspace missing, misaligned or smaller than sgap_reorder_rows_workspace_size");
+    const hipError_t err = launch_reorder_rows(M, K, rowptr, colidx, vals, order == SGAP_ORDER_BY_LENGTH, perm,
+                                               rowptr_out, colidx_out, vals_out, workspace, compute_units(), s);
+    if (err != hipSuccess) return fail(SGAP_ERR_HIP, "HIP launch failed: %s", hipGetErrorString(err));
+    return SGAP_OK;
+}
+
 int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, int64_t nnz, int64_t* report,
                       void* stream)
 {

@@ -230,6 +230,11 @@ hipError_t launch_mttkrp(int64_t I, int64_t K, int64_t L, int64_t J, const int32
                          int xcds, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
+// Rows grouped by a coarse key (sgap_reorder.hip): the permutation and the permuted copy of the matrix.
+int64_t reorder_workspace_bytes(int64_t M);
+hipError_t launch_reorder_rows(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                               bool by_length, int32_t* perm, int32_t* rowptr_out, int32_t* colidx_out,
+                               float* vals_out, void* workspace, int compute_units, hipStream_t s);
 
 // Generic (g, lc, vec) -> template instance dispatch.  F is a functor with
 //   template <int G, int LC, int VEC> void operator()() const

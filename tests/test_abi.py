@@ -309,6 +309,29 @@ def test_serial_plan_keeps_partial_sums_on_chip_and_fills_the_chip():
     assert lib.sgap_debug_plan_nnz_serial(3, 8, 4, 0, 256, 0, None, None, None) == binding.SGAP_ERR_INVALID_ARG
 
 
+def test_reordering_checks_its_arguments_on_the_host():
+    lib = binding.load()
+    size = lib.sgap_reorder_rows_workspace_size
+    assert size(-1) == -1
+    assert size(0) >= 256 and size(0) % 256 == 0
+    # two int32 per row, the key counters and a sum per block of rows
+    assert size(2_097_152) >= 8 * 2_097_152 + 8 * 4097 and size(2_097_152) % 256 == 0
+    assert size(10) <= size(11) <= size(100_000)
+    fake = ctypes.c_void_p(256)  # never dereferenced: every call below is refused before anything is launched
+    bad = [
+        dict(M=-1), dict(K=-1), dict(M=2**31), dict(order=2), dict(order=-1), dict(rowptr=None), dict(rowptr_out=None),
+        dict(perm=None), dict(K=0), dict(workspace=None), dict(workspace_bytes=100), dict(workspace=ctypes.c_void_p(264)),
+    ]
+    for change in bad:
+        a = dict(M=4, K=4, rowptr=fake, colidx=fake, vals=fake, order=0, perm=fake, rowptr_out=fake, colidx_out=fake,
+                 vals_out=fake, workspace=fake, workspace_bytes=1 << 20)
+        a.update(change)
+        rc = lib.sgap_reorder_rows_csr(a["M"], a["K"], a["rowptr"], a["colidx"], a["vals"], a["order"], a["perm"],
+                                       a["rowptr_out"], a["colidx_out"], a["vals_out"], a["workspace"],
+                                       a["workspace_bytes"], None)
+        assert rc == binding.SGAP_ERR_INVALID_ARG, change
+
+
 def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     # the boundary is a C ABI: the header must compile as C99 without warnings,
     # and a C program must link against the built library (it is not run: no GPU here)
