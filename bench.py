@@ -479,9 +479,18 @@ def reordered_rows(dp, torch, binding, C, cfg, ws, cfg_d):
         pre = launch_stats(torch, run, 5)
         dq = copy.copy(dp)
         dq.rowptr, dq.colidx, dq.vals = rowptr, colidx, vals
-        t = time_config(dq, torch, C, cfg, ws, 20)
-        out.append({"order": order, "preprocessing_ms": pre["median"], "ms_per_step": t * 1e3, "config": cfg_d})
-        log(f"[bench] {p.name}: rows by {order}: pass {pre['median']:.3f} ms, call {t * 1e3:.3f} ms")
+        # the configuration that won on the stored order, and the nnz-balanced serial points with more entries
+        # per lane (rows of one length now lie together)
+        best_t, best_c = time_config(dq, torch, C, cfg, ws, 20), cfg_d
+        for g in (16, 32, 64):
+            other = binding.make_config(g, "serial", "nnz_balanced")
+            if describe(other, binding) == cfg_d:
+                continue
+            t = time_config(dq, torch, C, other, None, 20)
+            if t < best_t:
+                best_t, best_c = t, describe(other, binding)
+        out.append({"order": order, "preprocessing_ms": pre["median"], "ms_per_step": best_t * 1e3, "config": best_c})
+        log(f"[bench] {p.name}: rows by {order}: pass {pre['median']:.3f} ms, call {best_t * 1e3:.3f} ms with {best_c}")
     return out
 
 
@@ -573,6 +582,20 @@ def measure_spmm(a, name, torch, binding, wl, copy_gbs):
     if a.sweep_out and sweep:
         with open(a.sweep_out.replace("{workload}", name), "w") as fh:
             json.dump({"workload": name, "stats": p.row_stats(), "points": sweep}, fh, indent=1)
+    if a.tuner_out:
+        # the library's own tuner (sgap_autotune_csr_cfg) over the space it has, with the working memory the
+        # window configurations at their defaults need
+        tune_ws = dp.workspace_for(binding.make_config(1, "serial", "row_split", long_row_min=1024))
+        t0 = time.perf_counter()
+        t_best, table = binding.sgap_autotune_csr_cfg(p.M, p.K, p.N, dp.rowptr, dp.colidx, dp.vals, dp.B, C,
+                                                      workspace=tune_ws)
+        log(f"[bench] {name}: tuner rated {len(table)} configurations in {time.perf_counter() - t0:.1f} s; "
+            f"best {describe(t_best.config, binding)} {t_best.ms:.3f} ms")
+        with open(a.tuner_out.replace("{workload}", name), "w") as fh:
+            json.dump({"workload": name, "stats": p.row_stats(),
+                       "best": {**describe(t_best.config, binding), "ms": t_best.ms},
+                       "table": [{**describe(t.config, binding), "ms": t.ms} for t in table]}, fh, indent=1)
+        del tune_ws
     del dp, C, ws
     torch.cuda.empty_cache()
     return rec
@@ -583,6 +606,8 @@ def main():
     ap.add_argument("--op", default="spmm", choices=("spmm", "sddmm", "mttkrp", "ttm"),
                     help="spmm (the headline path), sddmm on the same workload's pattern, or mttkrp / ttm on a "
                          "seeded third-order tensor")
+    ap.add_argument("--tuner-out", default=None,
+                    help="spmm: also run the library's tuner and write its table here as JSON ({workload} is replaced)")
     ap.add_argument("--no-reorder", action="store_true",
                     help="skip the leg that times the best configuration on the reordered copies of the matrix")
     ap.add_argument("--gpus", type=int, default=1)

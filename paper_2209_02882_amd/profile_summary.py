@@ -69,14 +69,14 @@ def read_run_dir(run_dir):
     return stats, counters, commands, bench
 
 
-SHAPE_KEYS = ("workload", "M", "K", "N", "nnz", "J", "rank")  # what bench.py adds to a configuration's description
+SHAPE_KEYS = ("workload", "op", "M", "K", "N", "nnz", "J", "I", "L", "fibers", "rank")  # what bench.py adds to a configuration's description
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("run_dir")
     ap.add_argument("--title", required=True)
-    ap.add_argument("--op", default="spmm")
+    ap.add_argument("--op", default=None, help="default: the one the run's bench.py line names, else spmm")
     ap.add_argument("--workload", default=None, help="default: the one the run's bench.py line names")
     ap.add_argument("--config", default=None,
                     help="JSON: the configuration as bench.py describes it (default: the one of the run's bench.py line)")
@@ -90,6 +90,10 @@ def main():
     named = dict(bench.get("config", {})) if bench else {}
     if a.workload is None:
         a.workload = named.get("workload")
+    if a.op is None:
+        a.op = named.get("op", "spmm")
+    if named.get("long_row_min") == 0:
+        del named["long_row_min"]
     for shape in SHAPE_KEYS:
         named.pop(shape, None)
     config = json.loads(a.config) if a.config else named
