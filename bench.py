@@ -306,7 +306,8 @@ def main_tensor(a):
     """--op mttkrp / --op ttm: the third-order operators on a seeded random
     tensor (--workload tensor3 unless another tensor workload is named), same
     JSON contract.  TTM along the third index is SpMM over the stored fibers,
-    so it sweeps all 28 SpMM points; MTTKRP sweeps (group_size, strategy)."""
+    so it sweeps all 28 SpMM points; MTTKRP sweeps its 28 (group_size, strategy,
+    schedule) points: slices or stored entries as the unit of work."""
     import torch
 
     import numpy as np
@@ -333,8 +334,9 @@ def main_tensor(a):
         out_t = torch.empty((p.I, p.J), dtype=torch.float32, device="cuda:0")
         min_bytes = p.mttkrp_minimal_bytes()
         flops = p.mttkrp_flops()
-        points = [(g, st) for st in ("parallel", "serial") for g in binding.GROUP_SIZES]
-        launch = lambda pt: dt.launch_mttkrp(out_t, *pt)
+        points = [(g, st, sc) for sc in ("row_split", "nnz_balanced") for st in ("parallel", "serial")
+                  for g in binding.GROUP_SIZES]
+        launch = lambda pt: dt.launch_mttkrp(out_t, *(pt if len(pt) == 3 else (*pt, "row_split")))
 
     def run(pt, n):
         for _ in range(n):
@@ -370,14 +372,12 @@ def main_tensor(a):
     kernel_avg_ms = kernel_ms / max(1, n_ev)
     achieved = min_bytes / (kernel_avg_ms * 1e-3) / 1e9
     copy_gbs = copy_reference(torch, binding)
-    key = {"group_size": best[0], "strategy": best[1]}
-    if ttm:
-        key["schedule"] = best[2]
+    if len(best) == 2:
+        best = (*best, "row_split")
+    key = {"group_size": best[0], "strategy": best[1], "schedule": best[2]}
     traffic, traffic_from = (None, "J was overridden") if a.ncols else measured_traffic(a.op, name, key)
     config = {"workload": name, "op": a.op, "I": p.I, "K": p.K, "L": p.L, "J": p.J, "fibers": p.fibers,
-              "nnz": p.nnz, "group_size": best[0], "strategy": best[1]}
-    if ttm:
-        config["schedule"] = best[2]
+              "nnz": p.nnz, "group_size": best[0], "strategy": best[1], "schedule": best[2]}
     out = {
         "metric": ("TTM effective GFLOP/s (2*nnz*J/t)" if ttm else "MTTKRP effective GFLOP/s (2*(nnz+fibers)*J/t)")
                   + ", fp32, best point",

@@ -420,6 +420,32 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J,
                     int group_size, int strategy, void* stream);
 
 /*
+ * The same operator with a choice of schedule (Section 6's two schedules
+ * carried over to it):
+ *   SGAP_SCHED_ROW_SPLIT     slices are the unit of work: exactly
+ *                            sgap_mttkrp_csf (nnz_hint is not used)
+ *   SGAP_SCHED_NNZ_BALANCED  stored entries are the unit of work, in tiles of
+ *                            1,024, whatever slices and fibers they fall in (a
+ *                            tensor with a few huge slices keeps the chip
+ *                            busy).  parallel: G lanes hold G consecutive
+ *                            entries and run two segmented sums, keyed by
+ *                            fiber and then, over the fiber sums times their
+ *                            rows of X1, by slice.  serial: a lane walks G
+ *                            consecutive entries and closes fibers into the
+ *                            slice's sum and slices into Y where they end.
+ *                            Y is set to zero first and every run's sum is
+ *                            added with fp32 atomics: results agree from run
+ *                            to run within rounding only.
+ *   nnz_hint   the number of stored entries if the host knows it (sizes the
+ *              grid for small tensors), else -1
+ * Everything else, and the errors, as sgap_mttkrp_csf; an unknown schedule is
+ * SGAP_ERR_INVALID_ARG.
+ */
+int sgap_mttkrp_csf_ex(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* fptr, const int32_t* fidx,
+                       const int32_t* eptr, const int32_t* eidx, const float* vals, const float* X1, const float* X2,
+                       float* Y, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream);
+
+/*
  * Tuner over the design space: the paper closes (Section 8) by proposing that
  * the space be exposed as an auto-tuning interface, and Table 5 measures what
  * a per-matrix choice gains over the best fixed point.  Times every

@@ -52,6 +52,7 @@ EXPORTS = {
     "sgap_reorder_rows_csr": (_int, [_i64, _i64, _p, _p, _p, _int, _p, _p, _p, _p, _p, _i64, _p]),
     "sgap_ttm_csf": (_int, [_i64, _i64, _i64, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_mttkrp_csf": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _p]),
+    "sgap_mttkrp_csf_ex": (_int, [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p, _p, _int, _int, _int, _i64, _p]),
     "sgap_status_string": (ctypes.c_char_p, [_int]),
     "sgap_last_error": (ctypes.c_char_p, []),
     "sgap_version": (_int, []),
@@ -331,6 +332,30 @@ def sgap_mttkrp_csf(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, group_s
         _dev_ptr(eptr, torch.int32, "eptr"), _dev_ptr(eidx, torch.int32, "eidx"),
         _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"), _dev_ptr(X2, torch.float32, "X2"),
         _dev_ptr(Y, torch.float32, "Y"), int(group_size), int(strategy), _stream_ptr(stream)))
+
+
+def sgap_mttkrp_csf_ex(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, group_size, strategy, schedule,
+                       nnz_hint=None, stream=None) -> None:
+    """sgap_mttkrp_csf with a choice of schedule: slices (row-split) or stored entries (nnz-balanced) as the
+    unit of work.  nnz_hint defaults to the length of vals."""
+    import torch
+
+    if fptr.numel() != I + 1:
+        raise ValueError("fptr must have I+1 entries")
+    if eptr.numel() != fidx.numel() + 1:
+        raise ValueError("eptr must have one entry more than fidx")
+    if eidx.numel() != vals.numel():
+        raise ValueError("eidx and vals must have the same length")
+    if X1.numel() != K * J or X2.numel() != L * J or Y.numel() != I * J:
+        raise ValueError("X1 must hold K*J, X2 L*J and Y I*J elements")
+    if nnz_hint is None:
+        nnz_hint = vals.numel()
+    _check(load().sgap_mttkrp_csf_ex(
+        I, K, L, J, _dev_ptr(fptr, torch.int32, "fptr"), _dev_ptr(fidx, torch.int32, "fidx"),
+        _dev_ptr(eptr, torch.int32, "eptr"), _dev_ptr(eidx, torch.int32, "eidx"),
+        _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(X1, torch.float32, "X1"), _dev_ptr(X2, torch.float32, "X2"),
+        _dev_ptr(Y, torch.float32, "Y"), int(group_size), int(strategy), int(schedule), int(nnz_hint),
+        _stream_ptr(stream)))
 
 
 def sgap_validate_csr(M, K, rowptr, colidx, stream=None):

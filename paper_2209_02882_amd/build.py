@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsgap.so")
 SOURCES = [
-    "sgap_api.hip", "sgap_row_split.hip", "sgap_row_split_partial.hip", "sgap_sddmm.hip", "sgap_mttkrp.hip", "sgap_panels.hip", "sgap_wave_rows.hip", "sgap_reorder.hip",
+    "sgap_api.hip", "sgap_row_split.hip", "sgap_row_split_partial.hip", "sgap_sddmm.hip", "sgap_mttkrp.hip", "sgap_panels.hip", "sgap_wave_rows.hip", "sgap_reorder.hip", "sgap_mttkrp_nnz.hip",
     "sgap_nnz_parallel.hip", "sgap_nnz_parallel_g1.hip", "sgap_nnz_parallel_g2.hip",
     "sgap_nnz_parallel_g4_16.hip", "sgap_nnz_parallel_g8_32_64.hip",
     "sgap_nnz_serial.hip", "sgap_nnz_serial_lc1_2.hip", "sgap_nnz_serial_lc4_8.hip",

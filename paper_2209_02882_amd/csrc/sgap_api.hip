@@ -763,7 +763,17 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* f
                     const int32_t* eptr, const int32_t* eidx, const float* vals, const float* X1, const float* X2,
                     float* Y, int group_size, int strategy, void* stream)
 {
+    return sgap_mttkrp_csf_ex(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, group_size, strategy,
+                              SGAP_SCHED_ROW_SPLIT, -1, stream);
+}
+
+int sgap_mttkrp_csf_ex(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* fptr, const int32_t* fidx,
+                       const int32_t* eptr, const int32_t* eidx, const float* vals, const float* X1, const float* X2,
+                       float* Y, int group_size, int strategy, int schedule, int64_t nnz_hint, void* stream)
+{
     using namespace sgap;
+    if (schedule != SGAP_SCHED_ROW_SPLIT && schedule != SGAP_SCHED_NNZ_BALANCED)
+        return fail(SGAP_ERR_INVALID_ARG, "unknown schedule");
     if (I < 0 || K < 0 || L < 0 || J < 0) return fail(SGAP_ERR_INVALID_ARG, "negative dimension");
     if (I > 2147483646LL || K > 2147483647LL || L > 2147483647LL || J > 2147483647LL)
         return fail(SGAP_ERR_INVALID_ARG, "dimension exceeds int32 index range");
@@ -793,8 +803,20 @@ int sgap_mttkrp_csf(int64_t I, int64_t K, int64_t L, int64_t J, const int32_t* f
         if (g_profile && hipEventCreate(&ev) == hipSuccess) hipEventRecord(ev, s);
     };
     mark(ev0);
-    hipError_t err = launch_mttkrp(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, g, rows_per_slot, par, lc, vec,
-                                   g_xcd_remap == 0 ? 1 : kXcds, s);
+    hipError_t err;
+    if (schedule == SGAP_SCHED_NNZ_BALANCED) {
+        // every run's sum is added into Y: all of Y starts at zero (zero_rows_kernel with "every row")
+        SpmmArgs z{};
+        z.M = I; z.K = K; z.N = J; z.rowptr = fptr; z.C = Y;
+        err = launch_nnz_zero_rows(z, vec, -1, s);
+        if (err == hipSuccess) {
+            const MttkrpArgs m{I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y};
+            const int lanes = pow2_ceil_capped((J + vec - 1) / vec, par ? 64 / group_size : 64);
+            err = launch_mttkrp_nnz(m, group_size, par, lanes, vec, compute_units(), nnz_hint, s);
+        }
+    } else
+        err = launch_mttkrp(I, K, L, J, fptr, fidx, eptr, eidx, vals, X1, X2, Y, g, rows_per_slot, par, lc, vec,
+                            g_xcd_remap == 0 ? 1 : kXcds, s);
     if (ev0) {
         mark(ev1);
         if (ev1) g_events.emplace_back(ev0, ev1); else hipEventDestroy(ev0);

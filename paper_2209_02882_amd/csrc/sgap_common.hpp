@@ -22,6 +22,19 @@ struct SpmmArgs {
     int group;        // group_size
 };
 
+// A third-order tensor as compressed sparse fibers (first index dense) and the dense operands of MTTKRP.
+struct MttkrpArgs {
+    int64_t I, K, L, J;
+    const int32_t* __restrict__ fptr;
+    const int32_t* __restrict__ fidx;
+    const int32_t* __restrict__ eptr;
+    const int32_t* __restrict__ eidx;
+    const float* __restrict__ vals;
+    const float* __restrict__ X1;
+    const float* __restrict__ X2;
+    float* __restrict__ Y;
+};
+
 // Rows another kernel produces: when *count <= max_rows, rows of at least
 // min_len stored entries are neither computed nor written by the kernel that
 // is handed this.  count = nullptr: no row is left out.
@@ -230,6 +243,10 @@ hipError_t launch_mttkrp(int64_t I, int64_t K, int64_t L, int64_t J, const int32
                          int xcds, hipStream_t s);
 hipError_t launch_debug_group_seg_reduce(const float* in, const int32_t* span, float* out, int g, int lc,
                                          hipStream_t s);
+// MTTKRP with the stored entries as the unit of work (sgap_mttkrp_nnz.hip): g = lanes per segment group
+// (parallel) or entries per lane (serial); Y must hold zeros.
+hipError_t launch_mttkrp_nnz(const MttkrpArgs& a, int g, bool parallel, int lc, int vec, int compute_units,
+                             int64_t nnz_hint, hipStream_t s);
 // Rows grouped by a coarse key (sgap_reorder.hip): the permutation and the permuted copy of the matrix.
 int64_t reorder_workspace_bytes(int64_t M);
 hipError_t launch_reorder_rows(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx, const float* vals,

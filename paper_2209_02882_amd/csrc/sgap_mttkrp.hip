@@ -32,18 +32,6 @@
 
 namespace sgap {
 
-struct MttkrpArgs {
-    int64_t I, K, L, J;
-    const int32_t* __restrict__ fptr;
-    const int32_t* __restrict__ fidx;
-    const int32_t* __restrict__ eptr;
-    const int32_t* __restrict__ eidx;
-    const float* __restrict__ vals;
-    const float* __restrict__ X1;
-    const float* __restrict__ X2;
-    float* __restrict__ Y;
-};
-
 constexpr int kMttkrpDepth = 4;  // gathered rows of X2 in flight per lane when entries come straight from memory
 
 // LDS copies of a block of slices: its slice pointers, its fibers (second index

@@ -122,16 +122,17 @@ class DeviceTensor3:
         for name in ("fptr", "fidx", "eptr", "eidx", "vals", "X1", "X2"):
             setattr(self, name, torch.from_numpy(getattr(p, name)).to(dev))
 
-    def launch_mttkrp(self, Y, group, strategy, stream=None):
+    def launch_mttkrp(self, Y, group, strategy, schedule="row_split", stream=None):
         p = self.p
-        binding.sgap_mttkrp_csf(p.I, p.K, p.L, p.J, self.fptr, self.fidx, self.eptr, self.eidx, self.vals,
-                                self.X1, self.X2, Y, group, binding.STRATEGIES[strategy], stream=stream)
+        binding.sgap_mttkrp_csf_ex(p.I, p.K, p.L, p.J, self.fptr, self.fidx, self.eptr, self.eidx, self.vals,
+                                   self.X1, self.X2, Y, group, binding.STRATEGIES[strategy],
+                                   binding.SCHEDULES[schedule], stream=stream)
 
-    def run_mttkrp(self, group, strategy, poison=True):
+    def run_mttkrp(self, group, strategy, schedule="row_split", poison=True):
         Y = torch.empty((self.p.I, self.p.J), dtype=torch.float32, device=self.fptr.device)
         if poison:
             Y.fill_(float("nan"))
-        self.launch_mttkrp(Y, group, strategy)
+        self.launch_mttkrp(Y, group, strategy, schedule)
         torch.cuda.synchronize()
         return Y
 

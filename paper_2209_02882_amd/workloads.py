@@ -385,13 +385,18 @@ TENSOR_WORKLOADS = {
     "tensor3_small": (2001, 512, 256, 320, 32, 4.0, 12),
     "tensor3_small_int": (2001, 512, 256, 320, 32, 4.0, 12),
     "tensor3": (2002, 262_144, 65_536, 65_536, 32, 8.0, 16),
+    "tensor3_skewed": (2003, 262_144, 65_536, 65_536, 32, 4.0, 16),
 }
+# name -> (share of the slices that are heavy, their fewest and most fibers): slices that differ in size by four
+# orders of magnitude, the case the nnz-balanced schedule is for
+TENSOR_HEAVY_SLICES = {"tensor3_skewed": (0.001, 2_000, 20_000)}
 
 
 def make_tensor3(name: str, J: int | None = None) -> Tensor3Problem:
     """Seeded random tensor: the number of fibers of a slice is geometric with
     the given mean, minus one with probability 1/8 (so some slices are empty and
-    a few are many times longer than the mean); a fiber holds 1 .. longest entries,
+    a few are many times longer than the mean; tensor3_skewed: one slice in a thousand
+    has 2,000 to 20,000 fibers instead); a fiber holds 1 .. longest entries,
     uniformly; second and third indices are uniform distinct subsets."""
     if name not in TENSOR_WORKLOADS:
         raise KeyError(f"unknown tensor workload {name!r}; have {sorted(TENSOR_WORKLOADS)}")
@@ -401,6 +406,10 @@ def make_tensor3(name: str, J: int | None = None) -> Tensor3Problem:
     rng = np.random.Generator(np.random.PCG64(seed))
     fibers = rng.geometric(1.0 / mean_fibers, size=I).astype(np.int64)
     fibers -= rng.random(I) < 0.125
+    if name in TENSOR_HEAVY_SLICES:
+        share, fewest, most = TENSOR_HEAVY_SLICES[name]
+        heavy = rng.random(I) < share
+        fibers[heavy] = rng.integers(fewest, most + 1, size=int(heavy.sum()))
     fibers = np.minimum(fibers, K)
     fptr, fidx = csr_from_lengths(rng, fibers, K)
     entries = rng.integers(1, longest + 1, size=int(fptr[-1])).astype(np.int64)

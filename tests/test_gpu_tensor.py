@@ -13,7 +13,9 @@ from gpu_util import TOL, assert_close
 
 pytestmark = pytest.mark.gpu
 
-MTTKRP_POINTS = [(g, st) for st in ("parallel", "serial") for g in binding.GROUP_SIZES]
+# (group size, strategy, schedule): slices or stored entries as the unit of work
+MTTKRP_POINTS = [(g, st, sc) for sc in ("row_split", "nnz_balanced") for st in ("parallel", "serial")
+                 for g in binding.GROUP_SIZES]
 
 
 def mttkrp_reference(p, nthreads=8):
@@ -41,13 +43,14 @@ def test_mttkrp_every_point_matches_the_oracle(name, J):
     p = wl.make_tensor3(name, J=J)
     ref, bnd = mttkrp_reference(p)
     dt = DeviceTensor3(p)
-    for g, st in MTTKRP_POINTS:
-        print("  mttkrp", name, J, g, st, flush=True)
-        assert_close(dt.run_mttkrp(g, st), ref, bnd, exact=name.endswith("_int"), what=f"{name} J={J} g={g} {st}")
+    for g, st, sc in MTTKRP_POINTS:
+        print("  mttkrp", name, J, g, st, sc, flush=True)
+        assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, exact=name.endswith("_int"),
+                     what=f"{name} J={J} g={g} {st} {sc}")
 
 
 @pytest.mark.parametrize("case", ["one_slice", "long_fibers", "many_fibers", "ragged_tail", "all_empty",
-                                  "single_entries"])
+                                  "single_entries", "runs_without_entries", "several_tiles"])
 def test_mttkrp_shapes_at_the_edges(case):
     if case == "one_slice":
         p = tensor_from(1, 40, 50, 32, [7], [1, 3, 9, 2, 33, 1, 4], 1)
@@ -59,14 +62,24 @@ def test_mttkrp_shapes_at_the_edges(case):
         p = tensor_from(259, 80, 80, 12, [1, 0, 4, 2, 9, 0, 3] * 37, [1, 2, 3, 4, 5], 4, integer=True)
     elif case == "all_empty":
         p = tensor_from(300, 10, 10, 16, [0] * 300, [1], 5)
+    elif case == "runs_without_entries":
+        # more slices without fibers and more fibers without entries in a row than a pointer window of the
+        # nnz-balanced kernel holds (1,025), at the start, in the middle and at the end
+        fibers = [0] * 1500 + [3] + [0] * 2100 + [1400, 2] + [0] * 1100 + [5] + [0] * 1030
+        entries = [0] * 2 + [4] + [0] * 1200 + [1, 2, 9] + [0] * 190 + [3, 0, 0, 1]
+        p = tensor_from(len(fibers), 2000, 70, 32, fibers, entries, 7, integer=True)
+    elif case == "several_tiles":
+        # 5,000 and some entries: five tiles of the nnz-balanced kernel, the last one ragged; slices and fibers
+        # that straddle tile ends
+        p = tensor_from(91, 300, 500, 40, [1, 0, 7, 2, 19, 0, 3] * 13, [30, 1, 2, 90, 5, 41, 8, 3], 8, integer=True)
     else:
         p = tensor_from(1000, 50, 60, 8, [1] * 1000, [1], 6, integer=True)
     ref, bnd = mttkrp_reference(p)
     dt = DeviceTensor3(p)
-    exact = case in ("long_fibers", "ragged_tail", "single_entries")
-    for g, st in MTTKRP_POINTS:
-        print("  mttkrp", case, g, st, flush=True)
-        assert_close(dt.run_mttkrp(g, st), ref, bnd, exact=exact, what=f"{case} g={g} {st}")
+    exact = case in ("long_fibers", "ragged_tail", "single_entries", "runs_without_entries", "several_tiles")
+    for g, st, sc in MTTKRP_POINTS:
+        print("  mttkrp", case, g, st, sc, flush=True)
+        assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, exact=exact, what=f"{case} g={g} {st} {sc}")
 
 
 def test_mttkrp_unsorted_and_repeated_indices_just_add():
@@ -91,8 +104,8 @@ def test_mttkrp_unsorted_and_repeated_indices_just_add():
     p.fidx = fidx
     ref, bnd = mttkrp_reference(p)
     dt = DeviceTensor3(p)
-    for g, st in MTTKRP_POINTS:
-        assert_close(dt.run_mttkrp(g, st), ref, bnd, exact=True, what=f"unsorted g={g} {st}")
+    for g, st, sc in MTTKRP_POINTS:
+        assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, exact=True, what=f"unsorted g={g} {st} {sc}")
 
 
 def test_mttkrp_unaligned_operands_take_narrower_loads():
@@ -104,8 +117,9 @@ def test_mttkrp_unaligned_operands_take_narrower_loads():
     dt.X2 = pad[1:].view(p.L, p.J)
     dt.X2.copy_(torch.from_numpy(p.X2))
     assert dt.X2.data_ptr() % 16 == 4
-    for g, st in [(1, "parallel"), (8, "parallel"), (4, "serial")]:
-        assert_close(dt.run_mttkrp(g, st), ref, bnd, what=f"unaligned g={g} {st}")
+    for g, st, sc in [(1, "parallel", "row_split"), (8, "parallel", "row_split"), (4, "serial", "row_split"),
+                      (8, "parallel", "nnz_balanced"), (16, "serial", "nnz_balanced")]:
+        assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, what=f"unaligned g={g} {st} {sc}")
 
 
 def test_mttkrp_full_size():
@@ -113,9 +127,9 @@ def test_mttkrp_full_size():
     print(p.stats(), flush=True)
     ref, bnd = mttkrp_reference(p, nthreads=16)
     dt = DeviceTensor3(p)
-    for g, st in MTTKRP_POINTS:
-        print("  mttkrp full size", g, st, flush=True)
-        assert_close(dt.run_mttkrp(g, st), ref, bnd, what=f"tensor3 g={g} {st}")
+    for g, st, sc in MTTKRP_POINTS:
+        print("  mttkrp full size", g, st, sc, flush=True)
+        assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, what=f"tensor3 g={g} {st} {sc}")
 
 
 def test_mttkrp_rejects_bad_arguments():
@@ -127,6 +141,9 @@ def test_mttkrp_rejects_bad_arguments():
     with pytest.raises(binding.SgapError):
         binding.sgap_mttkrp_csf(p.I, p.K, p.L, p.J, dt.fptr, dt.fidx, dt.eptr, dt.eidx, dt.vals, dt.X1, dt.X2, Y,
                                 4, 7)
+    with pytest.raises(binding.SgapError):
+        binding.sgap_mttkrp_csf_ex(p.I, p.K, p.L, p.J, dt.fptr, dt.fidx, dt.eptr, dt.eidx, dt.vals, dt.X1, dt.X2, Y,
+                                   4, binding.SGAP_REDUCE_SERIAL, 2)
 
 
 @pytest.mark.parametrize("name", ["tensor3_small", "tensor3_small_int"])
