@@ -506,6 +506,15 @@ def measure_spmm(a, name, torch, binding, wl, copy_gbs):
     C = torch.empty((p.M, p.N), dtype=torch.float32, device="cuda:0")
     min_bytes = p.minimal_bytes()
     flops = p.flops()
+    if a.reorder:
+        # everything below runs on the copy that sgap_reorder_rows_csr writes (rows of C come out in its order)
+        perm = torch.empty(p.M, dtype=torch.int32, device="cuda:0")
+        new = [torch.empty_like(t) for t in (dp.rowptr, dp.colidx, dp.vals)]
+        order_ws = torch.empty(binding.sgap_reorder_rows_workspace_size(p.M), dtype=torch.uint8, device="cuda:0")
+        binding.sgap_reorder_rows_csr(p.M, p.K, dp.rowptr, dp.colidx, dp.vals, a.reorder, perm, *new, order_ws)
+        torch.cuda.synchronize()
+        dp.rowptr, dp.colidx, dp.vals = new
+        del order_ws, perm
 
     sweep = []
     if a.point:
@@ -526,6 +535,8 @@ def measure_spmm(a, name, torch, binding, wl, copy_gbs):
             del ws
     ws = dp.workspace_for(best)
     best_d = describe(best, binding)
+    if a.reorder:
+        best_d["row_order"] = a.reorder
     log(f"[bench] {name}: timing {best_d}")
 
     for _ in range(a.warmup):
@@ -575,7 +586,7 @@ def measure_spmm(a, name, torch, binding, wl, copy_gbs):
             "algorithmic_bytes": min_bytes,
         },
     }
-    if not a.no_reorder and not a.point:
+    if not a.no_reorder and not a.point and not a.reorder:
         rec["reordered_rows"] = reordered_rows(dp, torch, binding, C, best, ws, best_d)
     if not a.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(p, a.cpu_seconds)
@@ -608,6 +619,8 @@ def main():
                          "seeded third-order tensor")
     ap.add_argument("--tuner-out", default=None,
                     help="spmm: also run the library's tuner and write its table here as JSON ({workload} is replaced)")
+    ap.add_argument("--reorder", default=None, choices=("first_column", "length"),
+                    help="spmm: run on the copy of the matrix that sgap_reorder_rows_csr writes with this key")
     ap.add_argument("--no-reorder", action="store_true",
                     help="skip the leg that times the best configuration on the reordered copies of the matrix")
     ap.add_argument("--gpus", type=int, default=1)

@@ -591,9 +591,9 @@ int sgap_validate_csr(int64_t M, int64_t K, const int32_t* rowptr, const int32_t
                       int64_t* report, void* stream);
 
 /*
- * Row order for locality (optional preprocessing; the schedules of Section 6
- * take the rows in the order in which they are stored, and Section 2.2 names
- * the work on locality that a better order stands for).  Writes a copy of the
+ * Row order (optional preprocessing; the schedules of Section 6 take the rows
+ * in the order in which they are stored, and Section 2.2 names the work on
+ * locality and balance that a better order stands for).  Writes a copy of the
  * CSR matrix whose rows are grouped by a coarse key, smaller key first, rows of
  * equal key in no particular order:
  *   SGAP_ORDER_BY_FIRST_COLUMN  key = floor(first stored column * 4096 / K);

@@ -1,14 +1,20 @@
-// Row order for locality: an optional preprocessing pass that writes a copy of a CSR matrix whose rows are
-// grouped by a coarse key, so that rows a workgroup (or a die) works through together touch neighbouring rows
-// of B.  The schedules of Section 6 take the rows in the order in which they are stored; Section 2.2 names the
-// work on locality that this stands for.  The product comes out in the new row order: row j of C = A' * B is
-// row perm[j] of A * B.
+// Row order: an optional preprocessing pass that writes a copy of a CSR matrix whose rows are grouped by a
+// coarse key.  The schedules of Section 6 take the rows in the order in which they are stored, and what a
+// wavefront's lanes meet there decides how well they run together; Section 2.2 names the line of work on
+// locality and balance that a better order stands for.  The product comes out in the new row order: row j of
+// C = A' * B is row perm[j] of A * B.
 //
 // Keys (kOrderBuckets of them, smaller key first, any order inside a key):
 //   by first column: bucket of the row's first stored column, K columns cut into equal bucket ranges; rows
 //     without entries come last.  Rows that start in the same range of B meet in time.
 //   by length: longest rows first (all rows of at least kOrderBuckets - 1 entries share the first key), rows
-//     without entries last.  Long rows, whose entries spread over all of B, stop interrupting the short ones.
+//     without entries last.  Lanes of a wavefront then walk rows of one length, and the runs of rows without
+//     entries no longer lie between the others.
+// What it buys where it was measured (R-MAT, 2 M rows, 44 % of them without entries, nnz-balanced serial
+// schedule): 0.96 -> 0.71 ms with either key, at the SAME bytes fetched from HBM and 14 % fewer vector
+// instructions: the gain is in how alike the lanes' work is, not in cache reuse.  (Moving only the rows
+// without entries to the end gives 0.85 ms.)  A stencil in its natural order and uniform random columns gain
+// nothing.
 // A bucket sort in three steps: every workgroup counts its rows per key in LDS and takes a run of places per
 // key from the global counters with one returning atomic per key it holds (a returning atomic per row on a
 // counter that a million rows share would take a tenth of a second); the counters are summed up; every row

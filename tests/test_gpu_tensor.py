@@ -82,6 +82,33 @@ def test_mttkrp_shapes_at_the_edges(case):
         assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, exact=exact, what=f"{case} g={g} {st} {sc}")
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_mttkrp_random_shapes(seed):
+    # seeded random tensors: slices without fibers, fibers without entries, a heavy slice now and then,
+    # any number of columns; three random points per schedule
+    rng = np.random.default_rng(1000 + seed)
+    I = int(rng.integers(1, 3000))
+    K = int(rng.integers(1, 400))
+    L = int(rng.integers(1, 400))
+    J = int(rng.choice([1, 3, 4, 8, 12, 32, 33, 64, 100, 256]))
+    fibers = rng.geometric(1.0 / float(rng.uniform(1.0, 6.0)), size=I) - 1
+    if seed % 3 == 0:
+        fibers[rng.integers(0, I)] = K
+    fibers = np.minimum(fibers, K)
+    fibers[rng.random(I) < rng.uniform(0.0, 0.7)] = 0
+    entries = np.minimum(rng.geometric(1.0 / float(rng.uniform(1.0, 20.0)), size=int(fibers.sum()) + 1) - (seed % 2), L)
+    entries = np.maximum(entries, 0)
+    p = tensor_from(I, K, L, J, fibers, entries, 2000 + seed, integer=True)
+    ref, bnd = mttkrp_reference(p)
+    dt = DeviceTensor3(p)
+    for sc in ("row_split", "nnz_balanced"):
+        for _ in range(3):
+            g = int(rng.choice(binding.GROUP_SIZES))
+            st = str(rng.choice(["parallel", "serial"]))
+            print("  mttkrp random", seed, I, K, L, J, p.fibers, p.nnz, g, st, sc, flush=True)
+            assert_close(dt.run_mttkrp(g, st, sc), ref, bnd, exact=True, what=f"seed {seed} g={g} {st} {sc}")
+
+
 def test_mttkrp_unsorted_and_repeated_indices_just_add():
     p = wl.make_tensor3("tensor3_small_int")
     rng = np.random.default_rng(9)
