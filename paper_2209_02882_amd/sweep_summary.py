@@ -1,8 +1,8 @@
 """Markdown tables out of the JSON files that bench.py writes with --sweep-out and --tuner-out.
 
-    python -m paper_2209_02882_amd.sweep_summary spmm  --dir gpurun_out --out profiles/sweep_all_points.md W1 W2 ...
-    python -m paper_2209_02882_amd.sweep_summary tuner --dir gpurun_out --out profiles/tuner_table.md W1 W2 ...
-    python -m paper_2209_02882_amd.sweep_summary other --dir gpurun_out --out profiles/sweep_sddmm.md sddmm_W1 sddmm_W2 ...
+    python -m paper_2209_02882_amd.sweep_summary spmm  --dir OUT_DIR --out profiles/sweep_all_points.md W1 W2 ...
+    python -m paper_2209_02882_amd.sweep_summary tuner --dir OUT_DIR --out profiles/tuner_table.md W1 W2 ...
+    python -m paper_2209_02882_amd.sweep_summary other --dir OUT_DIR --out profiles/sweep_sddmm.md sddmm_W1 sddmm_W2 ...
 
 `spmm` reads sweep_W.json (every point bench.py timed: the 28 (group size, strategy, schedule) points, the
 row-split points with long rows by column windows, with --gr the points whose reduction is narrower than
@@ -137,7 +137,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("kind", choices=("spmm", "tuner", "other"))
     ap.add_argument("workloads", nargs="+")
-    ap.add_argument("--dir", default="gpurun_out")
+    ap.add_argument("--dir", default=".", help="where bench.py wrote the JSON files")
     ap.add_argument("--suffix", default="", help="file names are sweep_W<suffix>.json / tuner_W<suffix>.json")
     ap.add_argument("--title", default=None)
     ap.add_argument("--preamble", default="", help="text (the commands, what was measured) put under the title")
