@@ -286,14 +286,21 @@ __device__ __forceinline__ void merge_write_out(const SpmmArgs& a, const MergeBu
 template <typename K>
 inline int resident_per_cu(K kernel, int smem)
 {
-    // more dynamic LDS than the default limit of a launch has to be asked for (once per kernel, for the
-    // most any plan takes: the tile's staging area on top of kMergeLdsLimit)
-    if (smem > 48 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kMergeLdsLimit + 16 * 1024);
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, smem) != hipSuccess || n < 1) n = 1;
     return n;
+}
+
+// More dynamic LDS than the default limit of a launch (64 KB with the kernel's static LDS) has to be asked for.
+// `asked` is the caller's record, per kernel instance, of the most it has asked for so far: an instance runs
+// with different amounts (the slots of the merge rule depend on the group size), and the limit only grows.
+template <typename K>
+inline void ensure_dynamic_lds(K kernel, int smem, int& asked)
+{
+    if (smem <= 32 * 1024 || smem <= asked) return;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, smem) ==
+        hipSuccess)
+        asked = smem;
 }
 
 inline int persistent_grid(int per_cu, int compute_units, int64_t nnz_hint, int tile)

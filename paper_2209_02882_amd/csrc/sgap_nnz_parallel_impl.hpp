@@ -265,6 +265,8 @@ struct Launch {
     {
         constexpr int nslots = kParTile / G + 1;
         constexpr int smem = kParTile * (int)sizeof(TileEntry) + (MERGE ? nslots * (LC * VEC * 4 + 8) : 0);
+        static int asked = 0;
+        ensure_dynamic_lds(nnz_parallel_kernel<G, LC, VEC, OFF32, MERGE>, smem, asked);
         static const int per_cu = resident_per_cu(nnz_parallel_kernel<G, LC, VEC, OFF32, MERGE>, smem);
         const int grid = persistent_grid(per_cu, compute_units, nnz_hint, kParTile);
         hipLaunchKernelGGL((nnz_parallel_kernel<G, LC, VEC, OFF32, MERGE>), dim3(grid), dim3(kBlock), smem, s, a);

@@ -24,11 +24,14 @@ namespace sgap {
 
 // Multiply out the chunk [base, end) of the tile staged in s_A (slot s holds
 // position tile_start + s), whose rows are s_win[w.n_first .. w.n_last + 1]
-// relative to row_lb.  MERGE selects tile mode of the merge rule.
+// relative to row_lb: window index wi stands for row row_lb + wi, or, when
+// s_row is given (a window of the rows WITH entries only), for row s_row[wi].
+// MERGE selects tile mode of the merge rule.
 template <int LC, int VEC, bool OFF32, bool MERGE>
 __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& mb, const StagedEntry* __restrict__ s_A,
                                              const int32_t* __restrict__ s_win, const RowWindow& w, int32_t row_lb,
-                                             int32_t tile_start, int32_t base, int32_t end)
+                                             int32_t tile_start, int32_t base, int32_t end,
+                                             const int32_t* __restrict__ s_row = nullptr)
 {
     constexpr int kDepth = 8;  // gathered rows of B in flight per lane
     // How partial sums are added into the LDS slots.  With many chunk lanes per
@@ -94,8 +97,8 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                     if (p >= blk_end) continue;
                     acc.fma(e[u].val, b[u]);
                     if (p + 1 != row_end && p + 1 != blk_end) continue;
-                    // flush the run [run_begin, p] of row row_lb + wi
-                    const int32_t row = row_lb + wi;
+                    // flush the run [run_begin, p] of the row at window index wi
+                    const int32_t row = s_row ? s_row[wi] : row_lb + wi;
                     if constexpr (MERGE) {
                         if (run_begin == row_begin && p + 1 == row_end) {
                             // the run is the whole row
@@ -137,6 +140,53 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
     }
 }
 
+// A window of the rows WITH stored entries that the tile [tile_start, tile_end) touches, for tiles whose rows do
+// not fit the plain window (long runs of rows without entries, as at the sparse end of an R-MAT matrix: a tile of
+// 1,024 entries there spans up to 9,000 rows).  The workgroup scans rowptr from row_lb (the row of tile_start) on,
+// 256 rows at a time, and keeps (first position, row) of every row that has entries below tile_end; such rows
+// start at distinct positions, one of them at or before tile_start and the others inside the tile, so there are
+// no more of them than the tile has positions, and the arrays are sized for that.  Returns the number of rows kept;
+// s_win[0 .. n] and s_row[0 .. n) are ready on return.  Block-uniform.
+__device__ __forceinline__ int32_t load_compact_window(const SpmmArgs& a, int32_t row_lb, int32_t tile_end,
+                                                       int32_t* __restrict__ s_win, int32_t* __restrict__ s_row,
+                                                       int32_t* __restrict__ s_wave)
+{
+    const int32_t M = (int32_t)a.M;
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    int32_t n = 0;
+    for (int64_t r0 = row_lb;; r0 += kBlock) {
+        const int64_t r = r0 + tid;
+        int32_t lo = 0x7fffffff, hi = 0x7fffffff;
+        if (r < M) {
+            lo = a.rowptr[r];
+            hi = a.rowptr[r + 1];
+        }
+        const bool keep = r < M && hi > lo && lo < tile_end;
+        const unsigned long long mask = __ballot(keep);
+        __syncthreads();  // s_wave is free again
+        if (lane == 0) s_wave[wave] = (int32_t)__popcll(mask);
+        __syncthreads();
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const int32_t c = s_wave[w];
+            if (w < wave) before += c;
+            total += c;
+        }
+        if (keep) {
+            const int32_t j = n + before + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            s_win[j] = lo;
+            s_row[j] = (int32_t)r;
+        }
+        n += total;
+        // rows are looked at in order: once one starts at or beyond tile_end (or the matrix ends) no later one counts
+        if (__syncthreads_or(lo >= tile_end)) break;
+    }
+    if (tid == 0) s_win[n] = a.rowptr[s_row[n - 1] + 1];  // where the last kept row ends (n >= 1: row_lb has entries)
+    __syncthreads();
+    return n;
+}
+
 // EPT = tile / kBlock stored entries per thread held in registers between tiles.
 template <int LC, int VEC, bool OFF32, bool MERGE, int EPT>
 __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
@@ -144,7 +194,11 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
     constexpr int TILE = EPT * kBlock;
     constexpr int WPT = kWindowCap / kBlock + 1;  // rowptr window entries per thread (last one: thread 0 only)
     extern __shared__ __align__(16) unsigned char s_raw[];
-    __shared__ int32_t s_win[kWindowCap + 1];
+    // (the window of rows with entries holds up to one row per position of the tile)
+    constexpr int WIN = TILE > kWindowCap ? TILE : kWindowCap;
+    __shared__ int32_t s_win[WIN + 1];
+    __shared__ int32_t s_row[WIN];
+    __shared__ int32_t s_scan[kWavesPerBlock];
     __shared__ int32_t s_tile_row[kTileRowBatch];
     constexpr int WIDTH = LC * VEC;
 
@@ -224,15 +278,15 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
                 w.n_last = first_above(s_win, kWindowCap + 1, tile_end - 1) - 1;
                 serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, row_lb, tile_start, tile_start, tile_end);
             } else {
-                // long runs of rows without entries: cut the tile at row
-                // boundaries so that each chunk's rows fit the window
-                for (int32_t base = tile_start; base < tile_end;) {
-                    __syncthreads();
-                    const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
-                    serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, row_lb, tile_start, base, base + w.cnt);
-                    row_lb += w.n_last;
-                    base += w.cnt;
-                }
+                // long runs of rows without entries: a window of the rows with entries only, so that the tile
+                // still goes in one piece (cutting it at the ends of plain windows costs a window load and
+                // several barriers per cut, and R-MAT's sparse end needs up to nine cuts per tile)
+                __syncthreads();  // everyone has read the plain window
+                RowWindow w;
+                w.cnt = tile_end - tile_start;
+                w.n_first = 0;
+                w.n_last = load_compact_window(a, row_lb, tile_end, s_win, s_row, s_scan) - 1;
+                serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, 0, tile_start, tile_start, tile_end, s_row);
             }
             __syncthreads();  // tile and window fully consumed before they are overwritten
         }
@@ -257,6 +311,8 @@ struct Launch {
         const int smem = tile * (int)sizeof(StagedEntry) + (MERGE ? nslots * (LC * VEC * 4 + 8) : 0);
         static int cached[7];  // [log2 group] resident workgroups per CU of this instance, 0 = not asked yet
         int& per_cu = cached[a.log2_group];
+        static int asked = 0;  // most dynamic LDS this instance has been allowed so far
+        ensure_dynamic_lds(nnz_serial_kernel<LC, VEC, OFF32, MERGE, EPT>, smem, asked);
         if (per_cu == 0) per_cu = resident_per_cu(nnz_serial_kernel<LC, VEC, OFF32, MERGE, EPT>, smem);
         const int grid = persistent_grid(per_cu, compute_units, nnz_hint, tile);
         hipLaunchKernelGGL((nnz_serial_kernel<LC, VEC, OFF32, MERGE, EPT>), dim3(grid), dim3(kBlock), smem, s, a);
