@@ -94,6 +94,53 @@ __device__ __forceinline__ RowWindow load_row_window(const SpmmArgs& a, int32_t&
     return w;
 }
 
+// A window of the rows WITH stored entries that the tile [tile_start, tile_end) touches, for tiles whose rows do
+// not fit the plain window (long runs of rows without entries, as at the sparse end of an R-MAT matrix: a tile of
+// 1,024 entries there spans up to 9,000 rows).  The workgroup scans rowptr from row_lb (the row of tile_start) on,
+// 256 rows at a time, and keeps (first position, row) of every row that has entries below tile_end; such rows
+// start at distinct positions, one of them at or before tile_start and the others inside the tile, so there are
+// no more of them than the tile has positions, and the arrays are sized for that.  Returns the number of rows kept;
+// s_win[0 .. n] and s_row[0 .. n) are ready on return.  Block-uniform.
+__device__ __forceinline__ int32_t load_compact_window(const SpmmArgs& a, int32_t row_lb, int32_t tile_end,
+                                                       int32_t* __restrict__ s_win, int32_t* __restrict__ s_row,
+                                                       int32_t* __restrict__ s_wave)
+{
+    const int32_t M = (int32_t)a.M;
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    int32_t n = 0;
+    for (int64_t r0 = row_lb;; r0 += kBlock) {
+        const int64_t r = r0 + tid;
+        int32_t lo = 0x7fffffff, hi = 0x7fffffff;
+        if (r < M) {
+            lo = a.rowptr[r];
+            hi = a.rowptr[r + 1];
+        }
+        const bool keep = r < M && hi > lo && lo < tile_end;
+        const unsigned long long mask = __ballot(keep);
+        __syncthreads();  // s_wave is free again
+        if (lane == 0) s_wave[wave] = (int32_t)__popcll(mask);
+        __syncthreads();
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const int32_t c = s_wave[w];
+            if (w < wave) before += c;
+            total += c;
+        }
+        if (keep) {
+            const int32_t j = n + before + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            s_win[j] = lo;
+            s_row[j] = (int32_t)r;
+        }
+        n += total;
+        // rows are looked at in order: once one starts at or beyond tile_end (or the matrix ends) no later one counts
+        if (__syncthreads_or(lo >= tile_end)) break;
+    }
+    if (tid == 0) s_win[n] = a.rowptr[s_row[n - 1] + 1];  // where the last kept row ends (n >= 1: row_lb has entries)
+    __syncthreads();
+    return n;
+}
+
 // The whole workgroup looks for one row together: each round probes rowptr at
 // up to kBlock evenly spaced rows and keeps the stretch between the last
 // probe at or before `pos` and the next one (3 rounds for 2 M rows, where a

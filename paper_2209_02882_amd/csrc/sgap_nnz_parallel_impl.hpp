@@ -45,12 +45,17 @@ constexpr int kParDepth = 4;                   // steps issued together
 // tile_start from the entries a thread holds in registers (thread t holds
 // positions tile_start + t + i*kBlock).  LDS slot s holds position
 // tile_start + s; slots outside the chunk are marked invalid.  The rows of the
-// chunk are s_win[w.n_first .. w.n_last + 1] relative to row_lb.
+// chunk are s_win[w.n_first .. w.n_last + 1] relative to row_lb, or, when s_row is
+// given (a window of the rows with entries only), the rows s_row[wi]; s_row may
+// then lie inside s_tile: every thread has read its rows before any record is
+// written (a barrier in between, so the call is block-uniform in that case).
 __device__ __forceinline__ void build_records(const int32_t (&col)[kParEpt], const float (&val)[kParEpt],
                                               int32_t tile_start, int32_t base, int32_t end, const RowWindow& w,
                                               int32_t row_lb, int log2_group, int nslots,
-                                              const int32_t* __restrict__ s_win, TileEntry* __restrict__ s_tile)
+                                              const int32_t* __restrict__ s_win, TileEntry* s_tile,
+                                              const int32_t* s_row = nullptr)
 {
+    TileEntry rec[kParEpt];
 #pragma unroll
     for (int i = 0; i < kParEpt; ++i) {
         const int q = threadIdx.x + i * kBlock;
@@ -72,11 +77,14 @@ __device__ __forceinline__ void build_records(const int32_t (&col)[kParEpt], con
             meta |= slot << kMetaSlotShift;
             e.col = col[i];
             e.val = val[i];
-            e.row = row_lb + wi;
+            e.row = s_row ? s_row[wi] : row_lb + wi;
             e.meta = meta;
         }
-        s_tile[q] = e;
+        rec[i] = e;
     }
+    if (s_row) __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kParEpt; ++i) s_tile[threadIdx.x + i * kBlock] = rec[i];
 }
 
 // Multiply out the records staged in s_tile: a lane multiplies ONE stored
@@ -157,8 +165,11 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
 {
     extern __shared__ __align__(16) unsigned char s_raw[];
     __shared__ int32_t s_win[kWindowCap + 1];
+    __shared__ int32_t s_scan[kWavesPerBlock];
     __shared__ int32_t s_tile_row[kTileRowBatch];
     constexpr int WIDTH = LC * VEC;
+    static_assert(kParTile <= kWindowCap, "the window of rows with entries holds one row per position");
+    static_assert(kWindowCap * sizeof(int32_t) <= kParTile * sizeof(TileEntry), "those rows are staged in the record area");
 
     TileEntry* s_tile = reinterpret_cast<TileEntry*>(s_raw);
     MergeBuf mb;
@@ -232,19 +243,20 @@ __global__ __launch_bounds__(kBlock) void nnz_parallel_kernel(SpmmArgs a)
                 if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
                 parallel_chunk<G, LC, VEC, OFF32, MERGE>(a, mb, s_tile);
             } else {
-                // long runs of rows without entries: cut the tile at row
-                // boundaries so that each chunk's rows fit the window
-                for (int32_t base = tile_start; base < tile_end;) {
-                    __syncthreads();
-                    const RowWindow w = load_row_window(a, row_lb, base, tile_end - base, s_win);
-                    build_records(nx_col, nx_val, tile_start, base, base + w.cnt, w, row_lb, a.log2_group, mb.nslots,
-                                  s_win, s_tile);
-                    __syncthreads();
-                    parallel_chunk<G, LC, VEC, OFF32, MERGE>(a, mb, s_tile);
-                    row_lb += w.n_last;
-                    base += w.cnt;
-                }
+                // long runs of rows without entries: a window of the rows with entries only, so that the tile
+                // still goes in one piece (sgap_nnz_common.hpp).  The rows are staged in the record area, which is
+                // free until build_records fills it (no static LDS to spare beside the largest merge slots).
+                int32_t* s_row = reinterpret_cast<int32_t*>(s_tile);
+                __syncthreads();  // everyone has read the plain window
+                RowWindow w;
+                w.cnt = tile_end - tile_start;
+                w.n_first = 0;
+                w.n_last = load_compact_window(a, row_lb, tile_end, s_win, s_row, s_scan) - 1;
+                build_records(nx_col, nx_val, tile_start, tile_start, tile_end, w, 0, a.log2_group, mb.nslots, s_win,
+                              s_tile, s_row);
+                __syncthreads();
                 if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
+                parallel_chunk<G, LC, VEC, OFF32, MERGE>(a, mb, s_tile);
             }
         }
     }
