@@ -33,9 +33,12 @@
 namespace sgap {
 
 constexpr int kPanelMaxWindows = 511;  // column windows at most
+constexpr int kPanelDies = 8;          // dies of the chip (the window count is made a multiple of it)
 constexpr int kRankMaxRows = 8192;     // lists up to this length are sorted by row length (their lengths fit in LDS)
+constexpr int kSearchLanes = 4;        // lanes that look for one window pointer together
 
-// The workspace: a header, the list of long rows, the same list sorted by length, and the window pointers.
+// The workspace: a header, the list of long rows, the same list sorted by length, the rows' lengths, and the
+// window pointers.
 struct PanelHeader {
     uint32_t count;     // long rows found (may exceed the list's capacity: then the path is off)
     uint32_t next[15];  // per die: the next item nobody has taken yet
@@ -45,13 +48,14 @@ struct PanelView {
     PanelHeader* head;
     int32_t* rows;   // [cap]
     int32_t* order;  // [cap] the long rows from the longest to the shortest: order[q] indexes rows[]
+    int32_t* len;    // [cap] stored entries of rows[i]
     int32_t* ptr;    // [cap * (windows + 1)]: ptr[i * (windows + 1) + w] = first entry of long row i with column >= w * window_rows
     uint32_t cap;    // rows the list holds
 };
 
 int64_t panel_workspace_bytes(int64_t cap, int windows)
 {
-    const int64_t ints = 2 * cap + cap * (int64_t)(windows + 1);
+    const int64_t ints = 3 * cap + cap * (int64_t)(windows + 1);
     return (int64_t)sizeof(PanelHeader) + (ints * 4 + 255) / 256 * 256;
 }
 
@@ -64,7 +68,8 @@ PanelView panel_view(void* workspace, int64_t cap, int windows)
     v.head = reinterpret_cast<PanelHeader*>(base);
     v.rows = reinterpret_cast<int32_t*>(base + sizeof(PanelHeader));
     v.order = v.rows + cap;
-    v.ptr = v.order + cap;
+    v.len = v.order + cap;
+    v.ptr = v.len + cap;
     v.cap = (uint32_t)cap;
     (void)windows;
     return v;
@@ -89,10 +94,12 @@ __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, Pan
     const int wave = threadIdx.x / kWave;
     const int64_t row0 = (int64_t)blockIdx.x * (kBlock * kFindRows) + threadIdx.x;
     uint32_t mine = 0;  // bit j: row row0 + j * kBlock is long
+    int32_t len[kFindRows];
 #pragma unroll
     for (int j = 0; j < kFindRows; ++j) {
         const int64_t row = row0 + (int64_t)j * kBlock;
-        if (row < a.M && a.rowptr[row + 1] - a.rowptr[row] >= min_len) mine |= 1u << j;
+        len[j] = row < a.M ? a.rowptr[row + 1] - a.rowptr[row] : 0;
+        if (row < a.M && len[j] >= min_len) mine |= 1u << j;
     }
     const uint32_t cnt = (uint32_t)__popc(mine);
     uint32_t incl = cnt;  // long rows of this and the lower lanes of the wavefront
@@ -117,7 +124,10 @@ __global__ __launch_bounds__(kBlock) void panel_find_rows_kernel(SpmmArgs a, Pan
 #pragma unroll
     for (int j = 0; j < kFindRows; ++j) {
         if (!(mine & (1u << j))) continue;
-        if (i < scr.cap) scr.rows[i] = (int32_t)(row0 + (int64_t)j * kBlock);
+        if (i < scr.cap) {
+            scr.rows[i] = (int32_t)(row0 + (int64_t)j * kBlock);
+            scr.len[i] = len[j];
+        }
         ++i;
     }
 }
@@ -131,37 +141,61 @@ __device__ __forceinline__ int panel_share_begin(int xcd, int windows, int xcds)
 }
 
 template <int VEC>
-__global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelView scr, int windows,
-                                                                int32_t window_rows, int zero_rows, uint32_t few_from,
-                                                                int xcds)
+__device__ __forceinline__ void panel_pointers_body(const SpmmArgs& a, const PanelView& scr, int windows,
+                                                    int32_t window_rows, int zero_rows, uint32_t few_from, int xcds,
+                                                    bool ranked, uint32_t block, uint32_t blocks)
 {
     const uint32_t n = scr.head->count;
     if (n == 0 || n > scr.cap) return;
-    const int64_t threads = (int64_t)gridDim.x * kBlock;
-    const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t threads = (int64_t)blocks * kBlock;
+    const int64_t tid = (int64_t)block * kBlock + threadIdx.x;
     const int per_row = windows + 1;
     const bool few = n >= few_from;
     const int wanted = few ? xcds + 1 : per_row;
-    for (int64_t t = tid; t < (int64_t)n * wanted; t += threads) {
-        const int i = (int)(t / wanted);
-        const int w = few ? panel_share_begin((int)(t % wanted), windows, xcds) : (int)(t % wanted);
-        const int32_t row = scr.rows[i];
-        int32_t lo = a.rowptr[row], hi = a.rowptr[row + 1];
-        if (w < windows) {
-            // first entry whose column is >= the window's first column.  For any
-            // order of the columns this is monotone in w, starts at the row's first
-            // entry and (w == windows) ends at its end: the runs always partition the row.
-            const int64_t target = (int64_t)w * window_rows;
-            while (lo < hi) {
-                const int32_t mid = lo + (hi - lo) / 2;
-                if (a.colidx[mid] >= target) hi = mid;
-                else lo = mid + 1;
-            }
-        } else {
-            lo = hi;
+    const bool keep_order = !ranked || n > (uint32_t)kRankMaxRows;  // nobody sorts the list: the order of finding
+    // kSearchLanes lanes look for one pointer together: each round they probe the stretch that is left at
+    // kSearchLanes places and keep the piece in front of the first probe whose column is at or beyond the window's
+    // first column (seven rounds of loads for a row of 20,000 entries, where one lane's bisection takes fifteen;
+    // every round is a load from HBM, about a microsecond, and nothing else happens meanwhile.  More lanes per
+    // pointer need fewer rounds but, for the 45,000 pointers of 5,000 long rows, more threads than are resident
+    // at once: 16 lanes took longer than 4).  For any order of the columns the result is monotone in w, it is the row's first
+    // entry for w = 0 and (w == windows) its end: the runs always partition the row.
+    const int part = threadIdx.x % kSearchLanes;
+    const int shift = (threadIdx.x % kWave) / kSearchLanes * kSearchLanes;
+    const int64_t items = (int64_t)n * wanted;
+    const int64_t rounds = (items * kSearchLanes + threads - 1) / threads;  // the same for every thread: ballots inside
+    for (int64_t round = 0; round < rounds; ++round) {
+        const int64_t t = (tid + round * threads) / kSearchLanes;
+        const bool mine = t < items;
+        const int i = mine ? (int)(t / wanted) : 0;
+        const int w = !mine ? 0 : few ? panel_share_begin((int)(t % wanted), windows, xcds) : (int)(t % wanted);
+        int32_t lo = 0, hi = 0;
+        if (mine) {
+            const int32_t row = scr.rows[i];
+            lo = a.rowptr[row];
+            hi = lo + scr.len[i];
+            if (w >= windows) lo = hi;
         }
-        scr.ptr[(int64_t)i * per_row + w] = lo;
-        if (t % wanted == 0) scr.order[i] = i;  // until panel_rank_kernel sorts the list
+        const int64_t target = (int64_t)w * window_rows;
+        while (__any(lo < hi)) {
+            // probe j of kSearchLanes sits at lo + floor(span * (j + 1) / (kSearchLanes + 1)) < hi (in 32 bits)
+            const uint32_t span = (uint32_t)(hi - lo);
+            const uint32_t whole = span / (kSearchLanes + 1), rest = span % (kSearchLanes + 1);
+            auto place = [&](int j) { return lo + (int32_t)(whole * (uint32_t)j + rest * (uint32_t)j / (kSearchLanes + 1)); };
+            const bool at_or_beyond = lo < hi && a.colidx[place(part + 1)] >= target;
+            const uint32_t found = (uint32_t)(__ballot(at_or_beyond) >> shift) & ((1u << kSearchLanes) - 1u);
+            if (lo < hi) {
+                const int first = found ? __ffs((int)found) - 1 : kSearchLanes;  // probes in front of it are below
+                const int32_t new_lo = first > 0 ? place(first) + 1 : lo;
+                const int32_t new_hi = first < kSearchLanes ? place(first + 1) : hi;
+                lo = new_lo;
+                hi = new_hi;
+            }
+        }
+        if (mine && part == 0) {
+            scr.ptr[(int64_t)i * per_row + w] = lo;
+            if (keep_order && t % wanted == 0) scr.order[i] = i;
+        }
     }
     if (!zero_rows) return;
     const int64_t chunks = a.N / VEC;  // N % VEC == 0
@@ -323,28 +357,61 @@ __global__ __launch_bounds__(kBlock) void panel_long_rows_kernel(SpmmArgs a, Pan
 // kRankMaxRows rows keeps the order in which the rows were found (panel_pointers_kernel wrote it): with so
 // many rows every wavefront owns several dozen and their lengths average out.
 constexpr int kRankLanes = 16;
-__global__ __launch_bounds__(kBlock) void panel_rank_kernel(const int32_t* __restrict__ rowptr, PanelView scr)
+static_assert(kRankMaxRows % (kRankLanes * 4) == 0, "the padded list fits the LDS array");
+__device__ __forceinline__ void panel_rank_body(const PanelView& scr, int32_t* s_len, uint32_t block)
 {
-    __shared__ int32_t s_len[kRankMaxRows];
     const uint32_t n = scr.head->count;
     constexpr uint32_t rows_per_block = kBlock / kRankLanes;
-    if (n == 0 || n > scr.cap || n > (uint32_t)kRankMaxRows || blockIdx.x * rows_per_block >= n) return;
-    for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
-        const int32_t row = scr.rows[i];
-        s_len[i] = rowptr[row + 1] - rowptr[row];
+    if (n == 0 || n > scr.cap || n > (uint32_t)kRankMaxRows || block * rows_per_block >= n) return;
+    // (padded to a multiple of the unrolled stride with lengths no row has: they come before nobody)
+    constexpr uint32_t kStride = kRankLanes * 4;
+    const uint32_t n_pad = (n + kStride - 1) / kStride * kStride;  // <= kRankMaxRows, a multiple of kStride
+    constexpr int kAtOnce = 8;  // loads in flight per thread
+    for (uint32_t j0 = threadIdx.x; j0 < n_pad; j0 += kAtOnce * kBlock) {
+        int32_t len[kAtOnce];
+#pragma unroll
+        for (int u = 0; u < kAtOnce; ++u) {
+            const uint32_t j = j0 + (uint32_t)u * kBlock;
+            len[u] = j < n ? scr.len[j] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kAtOnce; ++u) {
+            const uint32_t j = j0 + (uint32_t)u * kBlock;
+            if (j < n_pad) s_len[j] = len[u];
+        }
     }
     __syncthreads();
-    const uint32_t i = blockIdx.x * rows_per_block + threadIdx.x / kRankLanes;
+    const uint32_t i = block * rows_per_block + threadIdx.x / kRankLanes;
     const uint32_t part = threadIdx.x % kRankLanes;
     const int32_t mine = i < n ? s_len[i] : 0;
     uint32_t before = 0;
-    for (uint32_t j = part; j < n; j += kRankLanes) {
-        const int32_t other = s_len[j];
-        before += (other > mine || (other == mine && j < i)) ? 1u : 0u;
+    for (uint32_t j0 = part; j0 < n_pad; j0 += kStride) {
+        int32_t other[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) other[u] = s_len[j0 + u * kRankLanes];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            before += (other[u] > mine || (other[u] == mine && j0 + u * kRankLanes < i)) ? 1u : 0u;
     }
 #pragma unroll
     for (int m = kRankLanes / 2; m >= 1; m /= 2) before += (uint32_t)__shfl_xor((int)before, m, kRankLanes);
     if (i < n && part == 0) scr.order[before] = (int32_t)i;
+}
+
+// One launch for both: the first pointer_blocks workgroups write the pointers (and the zeros), the others rank
+// the rows; neither reads what the other writes.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void panel_pointers_kernel(SpmmArgs a, PanelView scr, int windows,
+                                                                int32_t window_rows, int zero_rows, uint32_t few_from,
+                                                                int xcds, uint32_t pointer_blocks)
+{
+    __shared__ int32_t s_len[kRankMaxRows];
+    const bool ranked = gridDim.x > pointer_blocks;
+    if (blockIdx.x < pointer_blocks)
+        panel_pointers_body<VEC>(a, scr, windows, window_rows, zero_rows, few_from, xcds, ranked, blockIdx.x,
+                                 pointer_blocks);
+    else
+        panel_rank_body(scr, s_len, blockIdx.x - pointer_blocks);
 }
 
 constexpr int kOwnerBlock = 1024;  // one workgroup of 16 wavefronts per compute unit
@@ -538,6 +605,14 @@ void plan_panels(int64_t K, int64_t N, int64_t window_bytes, int* windows, int32
         rows = (K + w - 1) / w;
         w = (K + rows - 1) / rows;
     }
+    // A multiple of kPanelDies windows of equal size: the dies walk equal shares of the windows, and with
+    // 123 windows two of eight dies would walk 16 while the others walk 15 and wait.
+    if (w > kPanelDies) {
+        w = (w + kPanelDies - 1) / kPanelDies * kPanelDies;
+        if (w > kPanelMaxWindows) w = kPanelMaxWindows / kPanelDies * kPanelDies;
+        rows = (K + w - 1) / w;
+        w = (K + rows - 1) / rows;
+    }
     if (w < 1) w = 1;
     *windows = (int)w;
     *window_rows = (int32_t)rows;
@@ -557,13 +632,14 @@ void launch_panel_preparation(const SpmmArgs& a, const PanelView& scr, int windo
     constexpr int64_t rows_per_block = (int64_t)kBlock * kFindRows;
     hipLaunchKernelGGL(panel_find_rows_kernel, dim3((unsigned)((a.M + rows_per_block - 1) / rows_per_block)), dim3(kBlock),
                        0, s, a, scr, min_len);
-    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(compute_units * 4), dim3(kBlock), 0, s, a, scr, windows,
-                       window_rows, zero_rows ? 1 : 0, few_from, xcds);
+    const uint32_t pointer_blocks = (uint32_t)compute_units * 4;
+    uint32_t rank_blocks = 0;
     if (rank_rows) {
         const uint32_t rows = scr.cap < (uint32_t)kRankMaxRows ? scr.cap : (uint32_t)kRankMaxRows;
-        hipLaunchKernelGGL(panel_rank_kernel, dim3((rows + kBlock / kRankLanes - 1) / (kBlock / kRankLanes)), dim3(kBlock),
-                           0, s, a.rowptr, scr);
+        rank_blocks = (rows + kBlock / kRankLanes - 1) / (kBlock / kRankLanes);
     }
+    hipLaunchKernelGGL((panel_pointers_kernel<4>), dim3(pointer_blocks + rank_blocks), dim3(kBlock), 0, s, a, scr, windows,
+                       window_rows, zero_rows ? 1 : 0, few_from, xcds, pointer_blocks);
 }
 
 // Lane layout of the SpMM window kernels: chunk lanes for the columns of a tile (at most kPanelTileLanes * 4

@@ -48,9 +48,9 @@ def test_configuration_defaults_workspace_size_and_checks():
     assert size(1000, 1000, 64, c) == 0  # long rows are not set apart
     c.long_row_min = 512
     # automatic window: 3072 KiB of B = 12288 rows of 64 columns -> 1 window over K = 1000; default list of 8192 rows
-    assert size(1000, 1000, 64, c) == 256 + 4 * 8192 * (1 + 3)
+    assert size(1000, 1000, 64, c) == 256 + 4 * 8192 * (1 + 4)
     c.window_kb, c.max_long_rows = 16, 100
-    assert size(1000, 1000, 64, c) == 256 + (4 * 100 * (16 + 3) + 255) // 256 * 256  # 64 rows per window -> 16 windows
+    assert size(1000, 1000, 64, c) == 256 + (4 * 100 * (16 + 4) + 255) // 256 * 256  # 64 rows per window -> 16 windows
     assert size(1000, 1000, 62, c) == 0  # needs 16-byte loads
     c.schedule = binding.SGAP_SCHED_NNZ_BALANCED
     assert size(1000, 1000, 64, c) == 0
@@ -78,7 +78,7 @@ def test_configuration_defaults_workspace_size_and_checks():
         assert lib.sgap_spmm_csr_cfg(4, 4, 4, *ptrs, ctypes.byref(bad_c), -1, None, 0, None) == binding.SGAP_ERR_INVALID_ARG
     # the SDDMM twin
     sd = binding.sgap_sddmm_csr_workspace_size
-    assert sd(1000, 64) == 256 + 4 * 8192 * (1 + 3)  # 2048 KiB windows: 8192 rows of 64 columns
+    assert sd(1000, 64) == 256 + 4 * 8192 * (1 + 4)  # 2048 KiB windows: 8192 rows of 64 columns
     assert sd(1000, 16) == 0 and sd(1000, 260) == 0 and sd(1000, 66) == 0
     assert lib.sgap_sddmm_csr_workspace_size(-1, 64, 0, 0) == -1
     assert lib.sgap_sddmm_csr_windows(4, 4, 64, *ptrs, 0x6000, 8, 0, 10, 100, 0, 0, None, 0, None) == \

@@ -153,7 +153,7 @@ def test_workspace_is_required_sized_and_private_to_a_call(panels):
     cfg = panels.config(1, "serial", "row_split")
     need = binding.sgap_spmm_csr_workspace_size(p.M, p.K, p.N, cfg)
     windows = -(-K // (64 * 1024 // (N * 4)))
-    assert need == 256 + (4 * 2000 * (windows + 3) + 255) // 256 * 256
+    assert need == 256 + (4 * 2000 * (windows + 4) + 255) // 256 * 256
     C = dp.new_output(poison=True)
     for ws in (None, torch.empty(need - 1, dtype=torch.uint8, device="cuda:0")):
         with pytest.raises(binding.SgapError):
