@@ -94,6 +94,49 @@ __device__ __forceinline__ RowWindow load_row_window(const SpmmArgs& a, int32_t&
     return w;
 }
 
+// Cut the plain window of a tile (s_win[r] = rowptr[row_lb + r], r <= kWindowCap, with s_win[kWindowCap] >=
+// tile_end, and row_lb the row of the tile's first position) down, in place, to the rows with entries that start
+// below tile_end: on return s_win[0 .. n] holds their first positions (and the end of the last), s_row[0 .. n)
+// their rows; n is returned.  A kept row moves to a slot at or in front of its own, every round reads its kBlock
+// slots before any is written, and a slot that a later round still reads is only ever overwritten with the value
+// it holds (the next row with entries starts where this one ends).  Block-uniform; two barriers per kBlock rows.
+__device__ __forceinline__ int32_t compact_window(int32_t* __restrict__ s_win, int32_t* __restrict__ s_row,
+                                                  int32_t row_lb, int32_t tile_end, int32_t* __restrict__ s_wave)
+{
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    int32_t n = 0;
+    for (int32_t r0 = 0;; r0 += kBlock) {
+        const int32_t r = r0 + tid;
+        int32_t lo = 0x7fffffff, hi = 0x7fffffff;
+        if (r < kWindowCap) {
+            lo = s_win[r];
+            hi = s_win[r + 1];
+        }
+        const bool keep = hi > lo && lo < tile_end;
+        const unsigned long long mask = __ballot(keep);
+        if (lane == 0) s_wave[wave] = (int32_t)__popcll(mask);
+        // rows are looked at in order: once one starts at or beyond tile_end (or the window ends) no later one counts
+        const bool done = __syncthreads_or(lo >= tile_end);
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int v = 0; v < kWavesPerBlock; ++v) {
+            const int32_t c = s_wave[v];
+            if (v < wave) before += c;
+            total += c;
+        }
+        if (keep) {
+            const int32_t j = n + before + (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            s_win[j] = lo;
+            s_win[j + 1] = hi;
+            s_row[j] = row_lb + r;
+        }
+        n += total;
+        __syncthreads();  // written before the next round reads on (or the caller does); s_wave is free again
+        if (done) break;
+    }
+    return n;
+}
+
 // A window of the rows WITH stored entries that the tile [tile_start, tile_end) touches, for tiles whose rows do
 // not fit the plain window (long runs of rows without entries, as at the sparse end of an R-MAT matrix: a tile of
 // 1,024 entries there spans up to 9,000 rows).  The workgroup scans rowptr from row_lb (the row of tile_start) on,

@@ -118,8 +118,8 @@ __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& 
                     acc.zero();
                     if (p + 1 < blk_end) {
                         // next row with stored entries (there is one at or before the
-                        // chunk's last row): usually the very next row, else bisect
-                        // over the rows without entries
+                        // chunk's last row): the very next slot in a window of rows with
+                        // entries only, else bisect over the rows without entries
                         ++wi;
                         row_begin = row_end;
                         row_end = s_win[wi + 1];
@@ -223,24 +223,23 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
             // start bringing in the next tile of this batch
             if (j + 1 < j1) fetch_tile(deal.tile(j + 1), s_tile_row[j + 1 - j0]);
 
+            // The rows WITH entries of the tile, their first positions in s_win and their numbers in s_row: rows
+            // without entries (44 % of the rows of an R-MAT matrix, in runs of 3.5 on average) would cost a search
+            // of the window at the end of the row in front of them, and cutting a tile whose rows do not fit the
+            // plain window costs a window load and several barriers per cut (R-MAT's sparse end: up to nine cuts
+            // per tile).  One path for all tiles also keeps the kernel's code (serial_chunk is long) small.
+            RowWindow w;
+            w.cnt = tile_end - tile_start;
+            w.n_first = 0;
             if (s_win[kWindowCap] >= tile_end) {
-                // the window covers every row of the tile: one chunk
-                RowWindow w;
-                w.cnt = tile_end - tile_start;
-                w.n_first = first_above(s_win, kWindowCap + 1, tile_start) - 1;
-                w.n_last = first_above(s_win, kWindowCap + 1, tile_end - 1) - 1;
-                serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, row_lb, tile_start, tile_start, tile_end);
+                // the plain window covers every row of the tile: cut it down where it stands
+                w.n_last = compact_window(s_win, s_row, row_lb, tile_end, s_scan) - 1;
             } else {
-                // long runs of rows without entries: a window of the rows with entries only, so that the tile
-                // still goes in one piece (cutting it at the ends of plain windows costs a window load and
-                // several barriers per cut, and R-MAT's sparse end needs up to nine cuts per tile)
+                // long runs of rows without entries: read on in rowptr
                 __syncthreads();  // everyone has read the plain window
-                RowWindow w;
-                w.cnt = tile_end - tile_start;
-                w.n_first = 0;
                 w.n_last = load_compact_window(a, row_lb, tile_end, s_win, s_row, s_scan) - 1;
-                serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, 0, tile_start, tile_start, tile_end, s_row);
             }
+            serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, 0, tile_start, tile_start, tile_end, s_row);
             __syncthreads();  // tile and window fully consumed before they are overwritten
         }
     }
