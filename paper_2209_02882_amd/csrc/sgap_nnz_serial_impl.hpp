@@ -26,7 +26,7 @@ namespace sgap {
 // position tile_start + s), whose rows are s_win[w.n_first .. w.n_last + 1]
 // relative to row_lb: window index wi stands for row row_lb + wi, or, when
 // s_row is given (a window of the rows WITH entries only), for row s_row[wi].
-// MERGE selects tile mode of the merge rule.
+// MERGE selects tile mode of the merge rule; in that mode the function ends with a barrier.
 template <int LC, int VEC, bool OFF32, bool MERGE>
 __device__ __forceinline__ void serial_chunk(const SpmmArgs& a, const MergeBuf& mb, const StagedEntry* __restrict__ s_A,
                                              const int32_t* __restrict__ s_win, const RowWindow& w, int32_t row_lb,
@@ -240,7 +240,8 @@ __global__ __launch_bounds__(kBlock) void nnz_serial_kernel(SpmmArgs a)
                 w.n_last = load_compact_window(a, row_lb, tile_end, s_win, s_row, s_scan) - 1;
             }
             serial_chunk<LC, VEC, OFF32, MERGE>(a, mb, s_A, s_win, w, 0, tile_start, tile_start, tile_end, s_row);
-            __syncthreads();  // tile and window fully consumed before they are overwritten
+            // tile and window fully consumed before they are overwritten (tile mode ends with a barrier of its own)
+            if constexpr (!MERGE) __syncthreads();
         }
     }
 }
