@@ -185,6 +185,10 @@ def test_identity_returns_B():
     [1023, 1, 1024, 1025, 0, 0, 2047, 1],    # rows around tile boundaries
     [0] * 3000 + [7] + [0] * 3000 + [2000],  # many empty rows in a tile window
     [2] * 512 + [0] * 5000 + [3] * 700,      # long empty stretch mid-matrix
+    [1, 0] * 500 + [3] * 100,                # a tile's window: 1,000 rows, every other one without entries
+    [0, 1, 0, 0, 2] * 300,                   # 1,024 entries span 1,700 rows, the rows with entries scattered among them
+    [0] * 10 + [1, 1, 0] * 340 + [0] * 10,   # rows without entries first, last and in between
+    [1] * 1024 + [0] + [1] * 1024 + [0] * 2, # a row without entries exactly where a tile ends
 ])
 def test_row_shapes_at_boundaries(lengths):
     M = len(lengths)
