@@ -48,6 +48,13 @@
  *   - Semantics are OVERWRITE (C = A*B): rows without stored entries become
  *     +0, whatever C held before.  A row's result may be -0 or +0 where the
  *     exact sum is zero.
+ *   - Placement (speed only, never results): any 4-byte aligned addresses are
+ *     accepted (16-byte aligned B and C allow 16-byte loads).  Where rows of B
+ *     are gathered at random out of memory, the operands of one matrix are
+ *     served faster out of ONE allocation, packed one after the other, than
+ *     out of five allocations that each start on a large page boundary
+ *     (R-MAT with 2^21 rows and 50 M entries, N = 32: 0.70 against 0.86 ms for
+ *     the same bytes moved).
  */
 #ifndef SGAP_H
 #define SGAP_H
