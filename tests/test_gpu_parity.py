@@ -124,6 +124,21 @@ def test_integer_variants_are_exact_everywhere():
             assert_close(dp.run(*point), C_ref, BND, exact=True, what=f"{name}-int {ids(point)}")
 
 
+def test_operands_packed_into_one_allocation():
+    # bench.py's layout: rowptr, colidx, vals, B and C one after the other in one allocation at 512-byte
+    # boundaries (none of them on a page boundary of its own); the first output is the allocation's own C
+    for name, kw in [("powerlaw", {}), ("rmat", dict(scale_down=64))]:
+        p = wl.make_problem(name, **kw)
+        dp = DeviceProblem(p, arena=True)
+        C_ref, BND = full_reference(p)
+        C = dp.new_output()
+        assert C.data_ptr() == dp.B.data_ptr() + (p.K * p.N * 4 + 511) // 512 * 512
+        for point in POINTS:
+            assert_close(dp.run(*point, C=C), C_ref, BND, what=f"{name} packed {ids(point)}")
+        cfg = binding.make_config(4, "serial", "row_split", long_row_min=64)
+        assert_close(dp.run_cfg(cfg, C=C), C_ref, BND, what=f"{name} packed, window path")
+
+
 def test_atomic_paths_repeat_within_tolerance():
     p = wl.make_problem("powerlaw", scale_down=2)
     dp = DeviceProblem(p)
