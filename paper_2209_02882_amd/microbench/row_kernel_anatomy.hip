@@ -279,15 +279,15 @@ __global__ __launch_bounds__(320) void tile_loop_producer(const float4* __restri
 
 int run_producer(const float4* buf, const int32_t* rowptr, const int32_t* cols, const float* vals, float4* C, int64_t M, int per_cu, const char* what)
 {
-    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     const int tiles = (int)(M / kRows), blocks = 256 * per_cu;
     tile_loop_producer<<<blocks, 320>>>(buf, rowptr, cols, vals, C, tiles); CK(hipDeviceSynchronize());
     float best = 1e30f;
     for (int rep = 0; rep < 5; ++rep) {
-        hipEventRecord(e0);
+        CK(hipEventRecord(e0));
         tile_loop_producer<<<blocks, 320>>>(buf, rowptr, cols, vals, C, tiles);
-        hipEventRecord(e1); CK(hipEventSynchronize(e1));
-        float ms; hipEventElapsedTime(&ms, e0, e1);
+        CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+        float ms; CK(hipEventElapsedTime(&ms, e0, e1));
         if (ms < best) best = ms;
     }
     const double bytes = (double)M * kLen * 512;
@@ -347,13 +347,13 @@ __global__ __launch_bounds__(320) void beside_stream(const float4* __restrict__ 
 template <int STEP>
 int run_beside(const float4* buf, float* out, float4* C, const int32_t* cols, const float* vals, int per_cu)
 {
-    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     const int blocks = 256 * per_cu, iters = 1000000 / (blocks * kRows);
     beside_stream<STEP><<<blocks, 320>>>(buf, out, 64, 4, 1, C, cols, vals); CK(hipDeviceSynchronize());
-    hipEventRecord(e0);
+    CK(hipEventRecord(e0));
     beside_stream<STEP><<<blocks, 320>>>(buf, out, 64, iters, 7, C, cols, vals);
-    hipEventRecord(e1); CK(hipEventSynchronize(e1));
-    float ms; hipEventElapsedTime(&ms, e0, e1);
+    CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1));
     const double bytes = (double)blocks * 256 * 16 * kLen * iters;
     printf("step %d  resident, %d workgroups per CU, window 32.8 KB, row stored, a fifth wavefront reads the pairs (%d bytes per lane): %7.1f GB/s  %5.1f B/clk/CU\n",
            STEP, per_cu, STEP == 12 ? 4 : 16, bytes / ms / 1e6, bytes / (ms * 1e-3) / 2.4e9 / 256);
@@ -363,15 +363,15 @@ int run_beside(const float4* buf, float* out, float4* C, const int32_t* cols, co
 template <int STEP>
 int run_tile_loop(const float4* buf, const int32_t* rowptr, const int32_t* cols, const float* vals, float4* C, int64_t M, int per_cu, const char* what)
 {
-    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     const int tiles = (int)(M / kRows), blocks = 256 * per_cu;
     tile_loop<STEP><<<blocks, 256>>>(buf, rowptr, cols, vals, C, tiles); CK(hipDeviceSynchronize());
     float best = 1e30f;
     for (int rep = 0; rep < 5; ++rep) {
-        hipEventRecord(e0);
+        CK(hipEventRecord(e0));
         tile_loop<STEP><<<blocks, 256>>>(buf, rowptr, cols, vals, C, tiles);
-        hipEventRecord(e1); CK(hipEventSynchronize(e1));
-        float ms; hipEventElapsedTime(&ms, e0, e1);
+        CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+        float ms; CK(hipEventElapsedTime(&ms, e0, e1));
         if (ms < best) best = ms;
     }
     const double bytes = (double)M * kLen * 512;
@@ -384,14 +384,14 @@ template <int STEP>
 int run_resident(const float4* buf, float* out, uint32_t rows, int per_cu, float4* C = nullptr, const int32_t* cols = nullptr,
                  const float* vals = nullptr)
 {
-    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     // (step 8: blocks * 8 rows of C per turn; 69 turns of 1,792 workgroups stay inside the 1,000,000 rows)
     const int blocks = 256 * per_cu, iters = STEP == 0 ? 400 : STEP >= 8 ? 1000000 / (blocks * kRows) : 120;
     resident<STEP><<<blocks, 256>>>(buf, out, rows, 4, 1, C, cols, vals); CK(hipDeviceSynchronize());
-    hipEventRecord(e0);
+    CK(hipEventRecord(e0));
     resident<STEP><<<blocks, 256>>>(buf, out, rows, iters, 7, C, cols, vals);
-    hipEventRecord(e1); CK(hipEventSynchronize(e1));
-    float ms; hipEventElapsedTime(&ms, e0, e1);
+    CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1));
     const double loads = STEP == 0 ? 8.0 : (double)kLen;
     const double bytes = (double)blocks * 256 * 16 * loads * iters;
     printf("step %d  resident, %d workgroups per CU, window %6.1f KB%s: %7.1f GB/s  %5.1f B/clk/CU\n", STEP, per_cu, rows * 512 / 1e3,
@@ -404,15 +404,15 @@ int run_resident(const float4* buf, float* out, uint32_t rows, int per_cu, float
 template <int STEP>
 int run_short(const float4* buf, const int32_t* rowptr, const int32_t* cols, const float* vals, float4* C, float* out, int64_t M, const char* what)
 {
-    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     const int blocks = (int)(M / kRows);
     short_lived<STEP><<<blocks, 256>>>(buf, rowptr, cols, vals, C, out); CK(hipDeviceSynchronize());
     float best = 1e30f;
     for (int rep = 0; rep < 5; ++rep) {
-        hipEventRecord(e0);
+        CK(hipEventRecord(e0));
         short_lived<STEP><<<blocks, 256>>>(buf, rowptr, cols, vals, C, out);
-        hipEventRecord(e1); CK(hipEventSynchronize(e1));
-        float ms; hipEventElapsedTime(&ms, e0, e1);
+        CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+        float ms; CK(hipEventElapsedTime(&ms, e0, e1));
         if (ms < best) best = ms;
     }
     const double bytes = (double)M * kLen * 512;
